@@ -1,0 +1,183 @@
+/*
+ * libdualparal -- one GPU's share of DualParal's block-wise denoising, for AMD MI355X (gfx950).
+ *
+ * A "stage" is the model chunk E_theta_j that one device of the paper's device pipeline owns
+ * (Sec. 2, Eq. 1; Sec. 3.1): it receives the hidden tokens eps^{j-1} in R^{p x h} of one frame
+ * block, runs them through its consecutive DiT layers and emits eps^j (Sec. 3.2, Eq. 2).  Every
+ * layer keeps the self-attention key/value features of the block it processed last (the feature
+ * cache of Sec. 3.2); the next block attends over [cached K/V ; its own K/V].  A queue driver
+ * (Sec. 3.1) decides which block runs when and at which noise level.
+ *
+ * Conventions for every entry point
+ *  - C linkage, no exceptions; every call returns a DP_* status; dp_last_error() returns a
+ *    thread-local text for the last failure on the calling thread.
+ *  - "device" pointers are HIP device memory owned by the caller (e.g. torch tensors); "host"
+ *    pointers are ordinary host memory, borrowed only for the duration of the call.
+ *  - The library never allocates or frees device memory.  All device state of a stage lives in
+ *    the caller's workspace, which must outlive the handle.
+ *  - Calls that take a stream are asynchronous on it and ordered by it.  One handle is used on
+ *    one stream at a time.  `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *  - Element type of activations and weights is the config's dtype: DP_F32 (float) or DP_BF16
+ *    (bfloat16, upper half of an IEEE float).  Matrices are row-major [in, out].
+ */
+#ifndef DUALPARAL_H
+#define DUALPARAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dp_stage dp_stage_t; /* opaque, host memory, owned by the library */
+
+enum { DP_OK = 0, DP_EINVAL = -1, DP_ENOMEM = -2 /* workspace / output too small */,
+       DP_ESTATE = -3 /* call out of order */, DP_EHIP = -4 /* a HIP call failed */ };
+enum { DP_F32 = 0, DP_BF16 = 1 };
+
+/* Geometry of a stage.  All sizes in elements. */
+typedef struct {
+  int32_t n_layers;           /* consecutive DiT layers this stage owns (L/N of Sec. 2)            */
+  int32_t dim;                /* hidden size h                                                    */
+  int32_t n_heads, head_dim;  /* n_heads * head_dim == dim; head_dim is 64 or 128                 */
+  int32_t ffn_dim;
+  int32_t text_len, text_dim; /* text tokens; text_dim != dim adds a two-layer text MLP           */
+  int32_t tok_h, tok_w;       /* tokens per latent frame = tok_h * tok_w (H' x W' of Sec. 2)      */
+  int32_t max_block_frames;   /* largest block a forward may be given (Num_B [+ Num_C/2])         */
+  int32_t max_cache_frames;   /* largest number of cached frames (Num_C/2)                        */
+  int32_t max_abs_frames;     /* frame0 + n_frames never exceeds this (extent of the RoPE table)  */
+  int32_t dtype;              /* DP_F32 or DP_BF16                                                */
+  int32_t freq_dim;           /* width of the sinusoidal timestep features (even)                 */
+  float rope_theta;           /* rotary base, e.g. 1e4                                            */
+  float eps;                  /* LayerNorm / RMSNorm epsilon, e.g. 1e-6                           */
+  int32_t debug_taps;         /* nonzero: keep intermediate results of the last layer for dp_stage_peek */
+} dp_stage_config;
+
+/* Device pointers to one layer's weights (element type = dtype). */
+typedef struct {
+  const void* mod;                               /* [6, dim] rows: shift1, scale1, gate1, shift2, scale2, gate2 */
+  const void *wq, *bq, *wk, *bk, *wv, *bv;       /* self-attention projections [dim, dim] / [dim]  */
+  const void *gq, *gk;                           /* q / k RMSNorm gains over the full dim          */
+  const void *wo, *bo;
+  const void *ln3_g, *ln3_b;                     /* affine LayerNorm in front of cross-attention   */
+  const void *cwq, *cbq, *cgq, *cwk, *cbk, *cgk, *cwv, *cbv, *cwo, *cbo;
+  const void *w1, *b1, *w2, *b2;                 /* FFN [dim, ffn_dim], [ffn_dim], [ffn_dim, dim], [dim] */
+} dp_layer_weights;
+
+/* Device pointers to the stage-level weights plus a HOST array of per-layer structs. */
+typedef struct {
+  const void *wt1, *bt1;       /* [freq_dim, dim], [dim]   timestep MLP, first layer               */
+  const void *wt2, *bt2;       /* [dim, dim], [dim]                                                */
+  const void *wm, *bm;         /* [dim, 6*dim], [6*dim]    modulation head                         */
+  const void *wx1, *bx1;       /* [text_dim, dim], [dim]   text MLP (ignored when text_dim == dim) */
+  const void *wx2, *bx2;       /* [dim, dim], [dim]                                                */
+  const dp_layer_weights* layers; /* host array of n_layers entries                               */
+} dp_stage_weights;
+
+/* Bytes of device workspace a stage of this geometry needs (0 if the config is invalid). */
+size_t dp_stage_workspace_bytes(const dp_stage_config* cfg);
+
+/*
+ * Create a stage (Sec. 2: device j holds the chunk E_theta_j).  Lays the workspace out, repacks the
+ * weights it wants in another layout, builds the RoPE tables and runs the text side once per prompt:
+ * the optional text MLP and every layer's cross-attention keys/values.  The feature cache starts empty.
+ *   cfg, weights : host structs (borrowed); the device memory the weights point to must stay valid
+ *                  and unchanged for the life of the handle.
+ *   text         : device [text_len, text_dim].
+ *   workspace    : device, 256-byte aligned, at least dp_stage_workspace_bytes(cfg) bytes; owned by
+ *                  the caller, used exclusively by this handle until dp_stage_free.
+ * Errors: DP_EINVAL (null pointer, n_heads*head_dim != dim, unsupported head_dim, sizes the kernels
+ * cannot tile), DP_ENOMEM (workspace too small), DP_EHIP.
+ */
+int dp_stage_init(const dp_stage_config* cfg, const dp_stage_weights* weights, const void* text,
+                  void* workspace, size_t workspace_bytes, void* hip_stream, dp_stage_t** out);
+
+/*
+ * eps^j = E_theta_j(eps^{j-1}) for one frame block (Sec. 2 Eq. 1, Sec. 3.2 Eq. 2).  For each layer:
+ * adaLN-modulated LayerNorm, q/k/v projection with q/k RMSNorm and 3D RoPE at the block's absolute
+ * frame offset, self-attention of the block's tokens over [cached K/V ; the block's own K/V]
+ * (Sec. 3.2), gated output projection, cross-attention to the text tokens, gated modulated FFN.
+ * Cross-attention and FFN touch only the block's own tokens (Sec. 3.2).  The block's rotated keys and
+ * values stay in the workspace so that dp_cache_update can retain some of their frames.
+ *   x_in  : device [n_frames*tok_h*tok_w, dim], tokens frame-major then row-major.
+ *   x_out : device, same shape; may alias x_in.
+ *   n_frames in [1, max_block_frames]; frame0 >= 0 is the absolute index of the block's first frame,
+ *   frame0 + n_frames <= max_abs_frames; timestep is the block's noise level on the model's
+ *   timestep scale (e.g. 0..1000).
+ * Errors: DP_EINVAL (bad sizes / null), DP_EHIP.
+ */
+int dp_stage_forward(dp_stage_t* stage, const void* x_in, void* x_out, int32_t n_frames,
+                     int32_t frame0, float timestep, void* hip_stream);
+
+/*
+ * Feature cache hand-over (Sec. 3.2): in every layer, the cache becomes the rotated keys and the
+ * values of frames [first_frame, first_frame + n_frames) of the block the last dp_stage_forward
+ * processed (frame indices relative to that block).  The cached keys carry their absolute
+ * positions, so the next block may lie before or after them.  n_frames == 0 empties the cache.
+ * Errors: DP_ESTATE (no forward yet), DP_EINVAL (range outside the last block or above
+ * max_cache_frames), DP_EHIP.
+ */
+int dp_cache_update(dp_stage_t* stage, int32_t first_frame, int32_t n_frames, void* hip_stream);
+
+/* Queue schedule of block-wise denoising (Sec. 3.1, 3.2, 3.3). */
+enum { DP_ORDER_REVERSE = 0 /* tail to head, the paper's choice */, DP_ORDER_SEQUENTIAL = 1 /* head to tail */ };
+
+typedef struct {
+  int32_t T;                  /* denoising steps = number of noise levels                         */
+  int32_t block_num;          /* blocks in the video                                              */
+  int32_t num_b;              /* frames per block                                                 */
+  int32_t num_c;              /* context frames; a block reuses num_c/2 cached frames of its neighbour */
+  int32_t first_block_frames; /* frames of block 1 (Sec. 3.3: num_b + num_c/2); 0 means num_b     */
+  int32_t order;              /* DP_ORDER_*                                                       */
+  float t_max;                /* timestep of level T; level k maps to t_max * k / T               */
+} dp_sched_config;
+
+typedef struct {
+  int32_t step;               /* diffusion step, 1 .. T + block_num - 1                           */
+  int32_t block;              /* 1-based block index in video order                               */
+  int32_t level;              /* noise level before this pass, T (noisiest) .. 1                  */
+  float timestep;
+  int32_t frame0, n_frames;   /* absolute first frame and length of the block                     */
+  int32_t cache_block;        /* block whose K/V this pass attends to (processed just before); 0 = none */
+  int32_t cache_first, cache_frames; /* retained frames of cache_block, relative to its first frame */
+} dp_sched_entry;
+
+/*
+ * Host only.  Writes the block passes of the whole generation in execution order: block b enters
+ * the queue's tail at step b at level T, each step processes every queued block once (tail to head
+ * for DP_ORDER_REVERSE), each pass lowers the block's level by one, and a block leaves after its
+ * level-1 pass.  There are T * block_num passes.  *n_written receives the number of passes; if
+ * capacity is smaller the call writes nothing and returns DP_ENOMEM (out may then be NULL).
+ * Errors: DP_EINVAL (null cfg / n_written, non-positive sizes), DP_ENOMEM.
+ */
+int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry* out, int64_t capacity,
+                          int64_t* n_written);
+
+/* Bubble ratio of the device pipeline as the paper prints it: Eq. 3 / Eq. 4 for DP_ORDER_REVERSE
+ * (N <= block_num / N > block_num), Eq. 5 for DP_ORDER_SEQUENTIAL.  Host only.  Returns -1 on bad input. */
+double dp_bubble_ratio(int32_t n_devices, int32_t T, int32_t block_num, int32_t order);
+
+/* Test hook: copies an internal result to `dst` as float32, token-major [rows, dim].
+ *   what : DP_PEEK_*; layer is used by the K / V / cache / modulation peeks, the others refer to the
+ *          last layer the last forward ran (they need cfg.debug_taps for X_SELF / X_CROSS).
+ *   dst  : device float buffer of at least `capacity` floats; *rows receives the row count.
+ * Errors: DP_ESTATE, DP_EINVAL, DP_ENOMEM. */
+enum { DP_PEEK_K = 0, DP_PEEK_V = 1, DP_PEEK_CACHE_K = 2, DP_PEEK_CACHE_V = 3, DP_PEEK_Q = 4,
+       DP_PEEK_ATTN = 5, DP_PEEK_CROSS_ATTN = 6, DP_PEEK_X_SELF = 7, DP_PEEK_X_CROSS = 8,
+       DP_PEEK_MOD = 9 /* [6, dim] of `layer` */, DP_PEEK_TEXT_K = 10, DP_PEEK_TEXT_V = 11,
+       DP_PEEK_X_RES = 12 /* the fp32 residual stream after the last layer, before rounding to x_out */ };
+int dp_stage_peek(dp_stage_t* stage, int32_t what, int32_t layer, float* dst, int64_t capacity,
+                  int64_t* rows, void* hip_stream);
+
+/* Releases the host-side handle (device memory belongs to the caller).  NULL is allowed. */
+void dp_stage_free(dp_stage_t* stage);
+
+/* Text of the last error on this thread ("" if none).  The pointer stays valid until the next
+ * failing call on the same thread. */
+const char* dp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DUALPARAL_H */

@@ -1,0 +1,211 @@
+"""Thin ctypes binding of libdualparal.so: argument marshalling only.
+
+Every step of the stage runs in the library's HIP kernels; torch is used for
+device memory (weights, workspace, activations) and for the stream handle.
+There is no fallback: if the library has not been built, importing fails.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdualparal.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2505_21070_amd.build` "
+                      "(hipcc, gfx950); there is no fallback path")
+_lib = C.CDLL(LIB_PATH)
+
+DP_OK, DP_EINVAL, DP_ENOMEM, DP_ESTATE, DP_EHIP = 0, -1, -2, -3, -4
+DP_F32, DP_BF16 = 0, 1
+ORDER = {"reverse": 0, "sequential": 1}
+PEEK = dict(k=0, v=1, cache_k=2, cache_v=3, q=4, attn=5, cross_attn=6, x_self=7, x_cross=8, mod=9,
+            text_k=10, text_v=11, x_res=12)
+
+LAYER_FIELDS = ("mod", "wq", "bq", "wk", "bk", "wv", "bv", "gq", "gk", "wo", "bo", "ln3_g", "ln3_b",
+                "cwq", "cbq", "cgq", "cwk", "cbk", "cgk", "cwv", "cbv", "cwo", "cbo", "w1", "b1", "w2", "b2")
+STAGE_FIELDS = ("wt1", "bt1", "wt2", "bt2", "wm", "bm", "wx1", "bx1", "wx2", "bx2")
+
+
+class StageConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "dim", "n_heads", "head_dim", "ffn_dim", "text_len",
+                                         "text_dim", "tok_h", "tok_w", "max_block_frames", "max_cache_frames",
+                                         "max_abs_frames", "dtype", "freq_dim")] + \
+               [("rope_theta", C.c_float), ("eps", C.c_float), ("debug_taps", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in LAYER_FIELDS]
+
+
+class StageWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in STAGE_FIELDS] + [("layers", C.POINTER(LayerWeights))]
+
+
+class SchedConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("T", "block_num", "num_b", "num_c", "first_block_frames", "order")] + \
+               [("t_max", C.c_float)]
+
+
+class SchedEntry(C.Structure):
+    _fields_ = [("step", C.c_int32), ("block", C.c_int32), ("level", C.c_int32), ("timestep", C.c_float),
+                ("frame0", C.c_int32), ("n_frames", C.c_int32), ("cache_block", C.c_int32),
+                ("cache_first", C.c_int32), ("cache_frames", C.c_int32)]
+
+
+_lib.dp_stage_workspace_bytes.restype = C.c_size_t
+_lib.dp_stage_workspace_bytes.argtypes = [C.POINTER(StageConfig)]
+_lib.dp_stage_init.restype = C.c_int
+_lib.dp_stage_init.argtypes = [C.POINTER(StageConfig), C.POINTER(StageWeights), C.c_void_p, C.c_void_p, C.c_size_t,
+                               C.c_void_p, C.POINTER(C.c_void_p)]
+_lib.dp_stage_forward.restype = C.c_int
+_lib.dp_stage_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p]
+_lib.dp_cache_update.restype = C.c_int
+_lib.dp_cache_update.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+_lib.dp_blockwise_schedule.restype = C.c_int
+_lib.dp_blockwise_schedule.argtypes = [C.POINTER(SchedConfig), C.POINTER(SchedEntry), C.c_int64, C.POINTER(C.c_int64)]
+_lib.dp_bubble_ratio.restype = C.c_double
+_lib.dp_bubble_ratio.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+_lib.dp_stage_peek.restype = C.c_int
+_lib.dp_stage_peek.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.POINTER(C.c_int64), C.c_void_p]
+_lib.dp_stage_free.restype = None
+_lib.dp_stage_free.argtypes = [C.c_void_p]
+_lib.dp_last_error.restype = C.c_char_p
+_lib.dp_last_error.argtypes = []
+
+
+class DualParalError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where} failed with status {code}: {_lib.dp_last_error().decode()}")
+
+
+def last_error():
+    return _lib.dp_last_error().decode()
+
+
+def _check(code, where):
+    if code != DP_OK:
+        raise DualParalError(code, where)
+
+
+def make_config(cfg, max_block_frames=None, max_cache_frames=None, max_abs_frames=4096, debug_taps=0):
+    """cfg: dict as produced by synth.stage_config."""
+    c = StageConfig()
+    for n in ("n_layers", "dim", "n_heads", "head_dim", "ffn_dim", "text_len", "text_dim", "tok_h", "tok_w", "freq_dim"):
+        setattr(c, n, int(cfg[n]))
+    c.max_block_frames = int(max_block_frames if max_block_frames is not None else cfg["block_frames"])
+    c.max_cache_frames = int(max_cache_frames if max_cache_frames is not None else cfg["cache_frames"])
+    c.max_abs_frames = int(max_abs_frames)
+    c.dtype = DP_BF16 if cfg["dtype"] == "bf16" else DP_F32
+    c.rope_theta = float(cfg["rope_theta"])
+    c.eps = float(cfg["eps"])
+    c.debug_taps = int(debug_taps)
+    return c
+
+
+def workspace_bytes(config):
+    return int(_lib.dp_stage_workspace_bytes(C.byref(config)))
+
+
+def _stream_handle(stream):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+class Stage:
+    """One pipeline stage on the current device.  weights: {"stage": {...}, "layers": [{...}]} of device
+    tensors in the stage's dtype (contiguous, [in, out] matrices); text: device [text_len, text_dim]."""
+
+    def __init__(self, config, weights, text, stream=None):
+        self.config = config
+        self.torch_dtype = torch.bfloat16 if config.dtype == DP_BF16 else torch.float32
+        dev = text.device
+        assert dev.type == "cuda", "the stage runs on the GPU only"
+        self._keep = [weights, text]            # the library borrows this memory for the handle's life
+
+        def ptr(t, shape):
+            assert t.is_cuda and t.dtype == self.torch_dtype and t.is_contiguous() and tuple(t.shape) == tuple(shape), \
+                (tuple(t.shape), shape, t.dtype)
+            return t.data_ptr()
+
+        D, F, Td, fd = config.dim, config.ffn_dim, config.text_dim, config.freq_dim
+        sw = StageWeights()
+        shapes = dict(wt1=(fd, D), bt1=(D,), wt2=(D, D), bt2=(D,), wm=(D, 6 * D), bm=(6 * D,),
+                      wx1=(Td, D), bx1=(D,), wx2=(D, D), bx2=(D,))
+        for n in STAGE_FIELDS:
+            if n in weights["stage"]:
+                setattr(sw, n, ptr(weights["stage"][n], shapes[n]))
+        arr = (LayerWeights * config.n_layers)()
+        for i, lw in enumerate(weights["layers"]):
+            for n in LAYER_FIELDS:
+                shape = (6, D) if n == "mod" else (D, F) if n == "w1" else (F,) if n == "b1" else (F, D) if n == "w2" \
+                    else (D, D) if n in ("wq", "wk", "wv", "wo", "cwq", "cwk", "cwv", "cwo") else (D,)
+                setattr(arr[i], n, ptr(lw[n], shape))
+        sw.layers = arr
+        assert tuple(text.shape) == (config.text_len, Td) and text.dtype == self.torch_dtype and text.is_contiguous()
+        nbytes = workspace_bytes(config)
+        if nbytes == 0:
+            raise DualParalError(DP_EINVAL, "dp_stage_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        h = C.c_void_p()
+        self._h = None
+        _check(_lib.dp_stage_init(C.byref(config), C.byref(sw), text.data_ptr(), self.workspace.data_ptr(), nbytes,
+                                  _stream_handle(stream), C.byref(h)), "dp_stage_init")
+        self._h = h
+        self.tok = config.tok_h * config.tok_w
+
+    def forward(self, x_in, n_frames, frame0, timestep, out=None, stream=None):
+        assert x_in.is_cuda and x_in.dtype == self.torch_dtype and x_in.is_contiguous()
+        assert tuple(x_in.shape) == (n_frames * self.tok, self.config.dim), tuple(x_in.shape)
+        if out is None:
+            out = torch.empty_like(x_in)
+        assert out.shape == x_in.shape and out.dtype == x_in.dtype and out.is_contiguous() and out.is_cuda
+        _check(_lib.dp_stage_forward(self._h, x_in.data_ptr(), out.data_ptr(), n_frames, frame0, float(timestep),
+                                     _stream_handle(stream)), "dp_stage_forward")
+        return out
+
+    def cache_update(self, first_frame, n_frames, stream=None):
+        _check(_lib.dp_cache_update(self._h, first_frame, n_frames, _stream_handle(stream)), "dp_cache_update")
+
+    def peek(self, what, layer=0, stream=None):
+        max_rows = max(self.config.max_block_frames * self.tok, self.config.text_len, 6)
+        buf = torch.empty((max_rows, self.config.dim), dtype=torch.float32, device=self.workspace.device)
+        rows = C.c_int64()
+        _check(_lib.dp_stage_peek(self._h, PEEK[what], layer, buf.data_ptr(), buf.numel(), C.byref(rows),
+                                  _stream_handle(stream)), "dp_stage_peek")
+        return buf[: rows.value]
+
+    def close(self):
+        if self._h is not None:
+            _lib.dp_stage_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def blockwise_schedule(T, block_num, num_b, num_c, first_block_frames=0, t_max=1000.0, order="reverse"):
+    cfg = SchedConfig(T, block_num, num_b, num_c, first_block_frames, ORDER[order], t_max)
+    n = C.c_int64()
+    rc = _lib.dp_blockwise_schedule(C.byref(cfg), None, 0, C.byref(n))
+    if rc not in (DP_OK, DP_ENOMEM):
+        raise DualParalError(rc, "dp_blockwise_schedule")
+    arr = (SchedEntry * n.value)()
+    _check(_lib.dp_blockwise_schedule(C.byref(cfg), arr, n.value, C.byref(n)), "dp_blockwise_schedule")
+    return [{f: getattr(e, f) for f, _ in SchedEntry._fields_} for e in arr]
+
+
+def bubble_ratio(n_devices, T, block_num, order="reverse"):
+    return float(_lib.dp_bubble_ratio(n_devices, T, block_num, ORDER[order]))
+
+
+def weights_to_device(weights, dtype, device="cuda"):
+    """synth weights (fp32 CPU tensors holding values representable in `dtype`) -> device tensors of `dtype`."""
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    return {"stage": {k: v.to(device=device, dtype=td).contiguous() for k, v in weights["stage"].items()},
+            "layers": [{k: v.to(device=device, dtype=td).contiguous() for k, v in lw.items()} for lw in weights["layers"]]}

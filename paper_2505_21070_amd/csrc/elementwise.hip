@@ -1,0 +1,360 @@
+// Bandwidth-bound kernels of the stage: type conversion, fused LayerNorm+modulate, q/k RMSNorm with
+// 3D RoPE, V transposition, cache copies, the timestep-modulation vector and small utilities.
+#include "kernels.h"
+
+static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ---------------------------------------------------------------- conversions
+template <typename T>
+__global__ void k_to_f32(const T* __restrict__ in, float* __restrict__ out, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) out[i] = Elem<T>::ld(in + i);
+}
+template <typename T>
+__global__ void k_from_f32(const float* __restrict__ in, T* __restrict__ out, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) Elem<T>::st(out + i, in[i]);
+}
+template <typename T> void launch_to_f32(const T* in, float* out, int64_t n, hipStream_t st) {
+  if (n <= 0) return;
+  int grid = cdiv(n, 256); if (grid > 8192) grid = 8192;
+  k_to_f32<T><<<grid, 256, 0, st>>>(in, out, n);
+}
+template <typename T> void launch_from_f32(const float* in, T* out, int64_t n, hipStream_t st) {
+  if (n <= 0) return;
+  int grid = cdiv(n, 256); if (grid > 8192) grid = 8192;
+  k_from_f32<T><<<grid, 256, 0, st>>>(in, out, n);
+}
+template void launch_to_f32<float>(const float*, float*, int64_t, hipStream_t);
+template void launch_to_f32<bf16_t>(const bf16_t*, float*, int64_t, hipStream_t);
+template void launch_from_f32<float>(const float*, float*, int64_t, hipStream_t);
+template void launch_from_f32<bf16_t>(const float*, bf16_t*, int64_t, hipStream_t);
+
+__global__ void k_fill_zero(uint32_t* p, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0u;
+}
+void launch_fill_zero(void* p, size_t bytes, hipStream_t st) {   // bytes % 4 == 0
+  int64_t n = (int64_t)(bytes / 4);
+  if (n <= 0) return;
+  int grid = cdiv(n, 256); if (grid > 16384) grid = 16384;
+  k_fill_zero<<<grid, 256, 0, st>>>((uint32_t*)p, n);
+}
+
+// ---------------------------------------------------------------- LayerNorm + modulate
+// One wavefront per row; the row lives in registers (NCH float4 per lane), so x is read once.
+// Two-pass statistics (mean, then centred variance) in fp32.
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void k_ln_modulate(const float* __restrict__ x, T* __restrict__ out,
+                                                     int64_t S, int D, float eps,
+                                                     const float* __restrict__ mul,
+                                                     const float* __restrict__ add, float plus) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= S) return;
+  const float4* xr = (const float4*)(x + row * D);
+  const int nvec = D >> 2;
+  float4 v[NCH];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int idx = i * 64 + lane;
+    if (idx < nvec) { v[i] = xr[idx]; sum += (v[i].x + v[i].y) + (v[i].z + v[i].w); }
+    else v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  const float mean = wave_sum(sum) / (float)D;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int idx = i * 64 + lane;
+    if (idx < nvec) {
+      const float a = v[i].x - mean, b = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
+      sq += (a * a + b * b) + (c * c + d * d);
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)D + eps);
+  T* orow = out + row * D;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int idx = i * 64 + lane;
+    if (idx < nvec) {
+      const float4 m = ((const float4*)mul)[idx];
+      const float4 a = ((const float4*)add)[idx];
+      const float r0 = (v[i].x - mean) * rstd * (m.x + plus) + a.x;
+      const float r1 = (v[i].y - mean) * rstd * (m.y + plus) + a.y;
+      const float r2 = (v[i].z - mean) * rstd * (m.z + plus) + a.z;
+      const float r3 = (v[i].w - mean) * rstd * (m.w + plus) + a.w;
+      if constexpr (sizeof(T) == 2) {
+        uint2 pk; pk.x = pack_bf16x2(r0, r1); pk.y = pack_bf16x2(r2, r3);
+        ((uint2*)orow)[idx] = pk;
+      } else {
+        ((float4*)orow)[idx] = make_float4(r0, r1, r2, r3);
+      }
+    }
+  }
+}
+template <typename T>
+void launch_ln_modulate(const float* x, T* out, int64_t S, int D, float eps, const float* mul,
+                        const float* add, int plus_one, hipStream_t st) {
+  const int grid = cdiv(S, 4);
+  const float plus = plus_one ? 1.f : 0.f;
+  if (D <= 256) k_ln_modulate<T, 1><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);
+  else if (D <= 2048) k_ln_modulate<T, 8><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);
+  else k_ln_modulate<T, 32><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);   // D <= 8192
+}
+template void launch_ln_modulate<float>(const float*, float*, int64_t, int, float, const float*, const float*, int, hipStream_t);
+template void launch_ln_modulate<bf16_t>(const float*, bf16_t*, int64_t, int, float, const float*, const float*, int, hipStream_t);
+
+// ---------------------------------------------------------------- RMSNorm over D + 3D RoPE, head-major output
+// One block per token.  Each thread owns channel pairs (2p, 2p+1), p = tid, tid + 256, ...
+template <typename T>
+__global__ __launch_bounds__(256) void k_norm_rope(const T* __restrict__ src, int64_t ld, int col, int h,
+                                                   int d, float eps, const float* __restrict__ g,
+                                                   T* __restrict__ dst, int64_t head_stride, int64_t row0,
+                                                   RopeTables rt, int use_rope, int frame0, int tok_h,
+                                                   int tok_w) {
+  __shared__ float red[4];
+  const int64_t s = blockIdx.x;
+  const int D = h * d, npair = D >> 1;
+  const T* row = src + s * ld + col;
+  float sq = 0.f;
+  for (int p = threadIdx.x; p < npair; p += 256) {
+    const float a = Elem<T>::ld(row + 2 * p), b = Elem<T>::ld(row + 2 * p + 1);
+    sq += a * a + b * b;
+  }
+  sq = wave_sum(sq);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
+  __syncthreads();
+  const float r = rsqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)D + eps);
+  const int tok = tok_h * tok_w;
+  const int f = frame0 + (int)(s / tok), rem = (int)(s % tok);
+  const int y = rem / tok_w, x = rem % tok_w;
+  const int half = d >> 1;
+  for (int p = threadIdx.x; p < npair; p += 256) {
+    const int head = p / half, i = p % half;
+    float a = Elem<T>::ld(row + 2 * p) * r * g[2 * p];
+    float b = Elem<T>::ld(row + 2 * p + 1) * r * g[2 * p + 1];
+    if (use_rope) {
+      float2 cs;
+      if (i < rt.c_f) cs = rt.f[(int64_t)f * rt.c_f + i];
+      else if (i < rt.c_f + rt.c_h) cs = rt.y[y * rt.c_h + (i - rt.c_f)];
+      else cs = rt.x[x * rt.c_w + (i - rt.c_f - rt.c_h)];
+      const float a2 = a * cs.x - b * cs.y, b2 = a * cs.y + b * cs.x;
+      a = a2; b = b2;
+    }
+    T* o = dst + (int64_t)head * head_stride + (row0 + s) * d + 2 * i;
+    Elem<T>::st(o, a);
+    Elem<T>::st(o + 1, b);
+  }
+}
+template <typename T>
+void launch_norm_rope(const T* src, int64_t ld, int col, int64_t S, int h, int d, float eps,
+                      const float* g, T* dst, int64_t head_stride, int64_t row0,
+                      const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st) {
+  if (S <= 0) return;
+  RopeTables rt = rope ? *rope : RopeTables{nullptr, nullptr, nullptr, 0, 0, 0};
+  k_norm_rope<T><<<(int)S, 256, 0, st>>>(src, ld, col, h, d, eps, g, dst, head_stride, row0, rt,
+                                         rope ? 1 : 0, frame0, tok_h > 0 ? tok_h : 1, tok_w > 0 ? tok_w : 1);
+}
+template void launch_norm_rope<float>(const float*, int64_t, int, int64_t, int, int, float, const float*, float*, int64_t, int64_t, const RopeTables*, int, int, int, hipStream_t);
+template void launch_norm_rope<bf16_t>(const bf16_t*, int64_t, int, int64_t, int, int, float, const float*, bf16_t*, int64_t, int64_t, const RopeTables*, int, int, int, hipStream_t);
+
+// ---------------------------------------------------------------- V -> V^T (per head [d][L])
+// 64x64 tile through LDS: reads are contiguous along channels, writes along tokens.
+template <typename T>
+__global__ __launch_bounds__(256) void k_v_transpose(const T* __restrict__ src, int64_t ld, int col, int64_t S,
+                                                     int D, int d, T* __restrict__ vt, int64_t row_stride,
+                                                     int64_t col0) {
+  __shared__ T tile[64][65];
+  const int64_t s0 = (int64_t)blockIdx.x * 64;
+  const int c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4) {
+    const int64_t s = s0 + r;
+    const int c = c0 + tx;
+    tile[r][tx] = (s < S && c < D) ? src[s * ld + col + c] : (T)0;
+  }
+  __syncthreads();
+  for (int r = ty; r < 64; r += 4) {
+    const int c = c0 + r;           // channel
+    const int64_t s = s0 + tx;      // token
+    if (c < D && s < S) {
+      const int head = c / d, cc = c % d;
+      vt[((int64_t)head * d + cc) * row_stride + col0 + s] = tile[tx][r];
+    }
+  }
+}
+template <typename T>
+void launch_v_transpose(const T* src, int64_t ld, int col, int64_t S, int h, int d, T* vt,
+                        int64_t row_stride, int64_t col0, hipStream_t st) {
+  if (S <= 0) return;
+  dim3 grid(cdiv(S, 64), cdiv(h * d, 64));
+  k_v_transpose<T><<<grid, 256, 0, st>>>(src, ld, col, S, h * d, d, vt, row_stride, col0);
+}
+template void launch_v_transpose<float>(const float*, int64_t, int, int64_t, int, int, float*, int64_t, int64_t, hipStream_t);
+template void launch_v_transpose<bf16_t>(const bf16_t*, int64_t, int, int64_t, int, int, bf16_t*, int64_t, int64_t, hipStream_t);
+
+// ---------------------------------------------------------------- strided row copy (feature-cache hand-over)
+// Rows are copied in 16-byte pieces when src, dst, strides and length allow it.
+template <typename T, typename V>
+__global__ void k_copy2d(const T* __restrict__ src, int64_t src_stride, T* __restrict__ dst,
+                         int64_t dst_stride, int64_t len_v) {
+  const V* s = (const V*)(src + (int64_t)blockIdx.y * src_stride);
+  V* d = (V*)(dst + (int64_t)blockIdx.y * dst_stride);
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < len_v; i += stride) d[i] = s[i];
+}
+template <typename T>
+void launch_copy2d(const T* src, int64_t src_stride, T* dst, int64_t dst_stride, int64_t rows,
+                   int64_t len, hipStream_t st) {
+  if (rows <= 0 || len <= 0) return;
+  const int per = 16 / (int)sizeof(T);
+  const bool vec = ((uintptr_t)src % 16 == 0) && ((uintptr_t)dst % 16 == 0) && (src_stride % per == 0) &&
+                   (dst_stride % per == 0) && (len % per == 0);
+  // rows can exceed the grid.y limit only for absurd shapes; split defensively
+  for (int64_t r0 = 0; r0 < rows; r0 += 32768) {
+    const int64_t nr = rows - r0 < 32768 ? rows - r0 : 32768;
+    if (vec) {
+      const int64_t lv = len / per;
+      int gx = cdiv(lv, 256); if (gx > 64) gx = 64;
+      k_copy2d<T, uint4><<<dim3(gx, (unsigned)nr), 256, 0, st>>>(src + r0 * src_stride, src_stride,
+                                                                 dst + r0 * dst_stride, dst_stride, lv);
+    } else {
+      int gx = cdiv(len, 256); if (gx > 64) gx = 64;
+      k_copy2d<T, T><<<dim3(gx, (unsigned)nr), 256, 0, st>>>(src + r0 * src_stride, src_stride,
+                                                             dst + r0 * dst_stride, dst_stride, len);
+    }
+  }
+}
+template void launch_copy2d<float>(const float*, int64_t, float*, int64_t, int64_t, int64_t, hipStream_t);
+template void launch_copy2d<bf16_t>(const bf16_t*, int64_t, bf16_t*, int64_t, int64_t, int64_t, hipStream_t);
+
+// ---------------------------------------------------------------- weight repack: [K,N] -> [Npad,K]
+template <typename T>
+__global__ __launch_bounds__(256) void k_transpose_pad(const T* __restrict__ in, int64_t K, int64_t N,
+                                                       T* __restrict__ out, int64_t Npad) {
+  __shared__ T tile[64][65];
+  const int64_t k0 = (int64_t)blockIdx.x * 64, n0 = (int64_t)blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4) {
+    const int64_t k = k0 + r, n = n0 + tx;
+    tile[r][tx] = (k < K && n < N) ? in[k * N + n] : (T)0;
+  }
+  __syncthreads();
+  for (int r = ty; r < 64; r += 4) {
+    const int64_t n = n0 + r, k = k0 + tx;
+    if (n < Npad && k < K) out[n * K + k] = tile[tx][r];
+  }
+}
+template <typename T>
+void launch_transpose_pad(const T* in, int64_t K, int64_t N, T* out, int64_t Npad, hipStream_t st) {
+  dim3 grid(cdiv(K, 64), cdiv(Npad, 64));
+  k_transpose_pad<T><<<grid, 256, 0, st>>>(in, K, N, out, Npad);
+}
+template void launch_transpose_pad<float>(const float*, int64_t, int64_t, float*, int64_t, hipStream_t);
+template void launch_transpose_pad<bf16_t>(const bf16_t*, int64_t, int64_t, bf16_t*, int64_t, hipStream_t);
+
+// ---------------------------------------------------------------- timestep modulation vector
+__global__ void k_sinusoid(float t, int freq_dim, float* out) {
+  const int half = freq_dim >> 1;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= half) return;
+  const double w = pow(10000.0, -(double)i / (double)half);
+  const double a = (double)t * w;
+  out[i] = (float)cos(a);
+  out[half + i] = (float)sin(a);
+}
+void launch_sinusoid(float t, int freq_dim, float* out, hipStream_t st) {
+  k_sinusoid<<<cdiv(freq_dim / 2, 64), 64, 0, st>>>(t, freq_dim, out);
+}
+
+// y[n] = sum_k act(x[k]) W[k,n] + b[n].  One thread per output column, 4 independent partial sums.
+template <typename T>
+__global__ __launch_bounds__(256) void k_gemv(const float* __restrict__ x, int K, const T* __restrict__ W,
+                                              const T* __restrict__ b, int N, int silu_in,
+                                              float* __restrict__ y) {
+  extern __shared__ float xs[];
+  for (int k = threadIdx.x; k < K; k += 256) { const float v = x[k]; xs[k] = silu_in ? v / (1.0f + expf(-v)) : v; }
+  __syncthreads();
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+  int k = 0;
+  for (; k + 4 <= K; k += 4) {
+    a0 += xs[k] * Elem<T>::ld(W + (int64_t)k * N + n);
+    a1 += xs[k + 1] * Elem<T>::ld(W + (int64_t)(k + 1) * N + n);
+    a2 += xs[k + 2] * Elem<T>::ld(W + (int64_t)(k + 2) * N + n);
+    a3 += xs[k + 3] * Elem<T>::ld(W + (int64_t)(k + 3) * N + n);
+  }
+  for (; k < K; ++k) a0 += xs[k] * Elem<T>::ld(W + (int64_t)k * N + n);
+  y[n] = ((a0 + a1) + (a2 + a3)) + (b ? Elem<T>::ld(b + n) : 0.f);
+}
+template <typename T>
+void launch_gemv(const float* x, int K, const T* W, const T* b, int N, int silu_in, float* y, hipStream_t st) {
+  k_gemv<T><<<cdiv(N, 256), 256, (size_t)K * sizeof(float), st>>>(x, K, W, b, N, silu_in, y);
+}
+template void launch_gemv<float>(const float*, int, const float*, const float*, int, int, float*, hipStream_t);
+template void launch_gemv<bf16_t>(const float*, int, const bf16_t*, const bf16_t*, int, int, float*, hipStream_t);
+
+__global__ void k_mod_add(const float* __restrict__ mtab, const float* __restrict__ e0,
+                          float* __restrict__ mod, int L, int n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (int64_t)L * n) mod[i] = mtab[i] + e0[i % n];
+}
+void launch_mod_add(const float* mtab, const float* e0, float* mod, int L, int n, hipStream_t st) {
+  k_mod_add<<<cdiv((int64_t)L * n, 256), 256, 0, st>>>(mtab, e0, mod, L, n);
+}
+
+// cos/sin of pos * theta^(-i/pairs), angles in double
+__global__ void k_rope_table(float2* tab, int n_pos, int pairs, float theta) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_pos * pairs) return;
+  const int pos = i / pairs, j = i % pairs;
+  const double ang = (double)pos * pow((double)theta, -(double)j / (double)pairs);
+  tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+void launch_rope_table(float2* tab, int n_pos, int pairs, float theta, hipStream_t st) {
+  if (n_pos * pairs <= 0) return;
+  k_rope_table<<<cdiv((int64_t)n_pos * pairs, 256), 256, 0, st>>>(tab, n_pos, pairs, theta);
+}
+
+// ---------------------------------------------------------------- test-hook gathers (head-major -> token-major fp32)
+template <typename T>
+__global__ void k_gather_heads(const T* __restrict__ src, int64_t head_stride, int64_t row0, int64_t S,
+                               int h, int d, float* __restrict__ dst) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int D = h * d;
+  if (i >= S * D) return;
+  const int64_t s = i / D; const int c = (int)(i % D);
+  dst[i] = Elem<T>::ld(src + (int64_t)(c / d) * head_stride + (row0 + s) * d + (c % d));
+}
+template <typename T>
+void launch_gather_heads(const T* src, int64_t head_stride, int64_t row0, int64_t S, int h, int d,
+                         float* dst, hipStream_t st) {
+  if (S <= 0) return;
+  k_gather_heads<T><<<cdiv(S * h * d, 256), 256, 0, st>>>(src, head_stride, row0, S, h, d, dst);
+}
+template void launch_gather_heads<float>(const float*, int64_t, int64_t, int64_t, int, int, float*, hipStream_t);
+template void launch_gather_heads<bf16_t>(const bf16_t*, int64_t, int64_t, int64_t, int, int, float*, hipStream_t);
+
+template <typename T>
+__global__ void k_gather_vt(const T* __restrict__ vt, int64_t row_stride, int64_t col0, int64_t S, int h,
+                            int d, float* __restrict__ dst) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int D = h * d;
+  if (i >= S * D) return;
+  const int64_t s = i / D; const int c = (int)(i % D);
+  dst[i] = Elem<T>::ld(vt + (int64_t)c * row_stride + col0 + s);
+}
+template <typename T>
+void launch_gather_vt(const T* vt, int64_t row_stride, int64_t col0, int64_t S, int h, int d, float* dst,
+                      hipStream_t st) {
+  if (S <= 0) return;
+  k_gather_vt<T><<<cdiv(S * h * d, 256), 256, 0, st>>>(vt, row_stride, col0, S, h, d, dst);
+}
+template void launch_gather_vt<float>(const float*, int64_t, int64_t, int64_t, int, int, float*, hipStream_t);
+template void launch_gather_vt<bf16_t>(const bf16_t*, int64_t, int64_t, int64_t, int, int, float*, hipStream_t);

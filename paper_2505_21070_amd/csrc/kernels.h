@@ -1,0 +1,71 @@
+// Host-side launchers of libdualparal's kernels.  Every launcher only enqueues work on `st`.
+#pragma once
+#include "common.h"
+
+// ---- elementwise.hip -------------------------------------------------------------------------
+template <typename T> void launch_to_f32(const T* in, float* out, int64_t n, hipStream_t st);
+template <typename T> void launch_from_f32(const float* in, T* out, int64_t n, hipStream_t st);
+// out[s,:] = LayerNorm(x[s,:]) * (mul + plus_one) + add ; x fp32 [S,D], mul/add fp32 [D]
+template <typename T>
+void launch_ln_modulate(const float* x, T* out, int64_t S, int D, float eps, const float* mul,
+                        const float* add, int plus_one, hipStream_t st);
+
+struct RopeTables {            // cos/sin pairs: tab[pos][pair] = (cos, sin)
+  const float2* f; const float2* y; const float2* x;
+  int c_f, c_h, c_w;           // pairs per axis
+};
+// One source matrix src[S, ld] holding an un-normalised projection in columns [col, col+D).
+// dst[head][row0 + s][d] = RoPE(RMSNorm_D(src[s]) * g) ; rope == nullptr skips the rotation.
+template <typename T>
+void launch_norm_rope(const T* src, int64_t ld, int col, int64_t S, int h, int d, float eps,
+                      const float* g, T* dst, int64_t head_stride, int64_t row0,
+                      const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st);
+// vt[head][c][col0 + s] = src[s, col + head*d + c]
+template <typename T>
+void launch_v_transpose(const T* src, int64_t ld, int col, int64_t S, int h, int d, T* vt,
+                        int64_t row_stride, int64_t col0, hipStream_t st);
+// dst[r][0..len) = src[r][0..len) for r < rows (strides in elements)
+template <typename T>
+void launch_copy2d(const T* src, int64_t src_stride, T* dst, int64_t dst_stride, int64_t rows,
+                   int64_t len, hipStream_t st);
+// out[n, k] = in[k, n] for n < N, zero rows for N <= n < Npad     (in [K, N] row-major)
+template <typename T>
+void launch_transpose_pad(const T* in, int64_t K, int64_t N, T* out, int64_t Npad, hipStream_t st);
+
+void launch_sinusoid(float t, int freq_dim, float* out, hipStream_t st);
+// y[n] = sum_k act(x[k]) * W[k, n] + b[n] ; act = SiLU when silu_in
+template <typename T>
+void launch_gemv(const float* x, int K, const T* W, const T* b, int N, int silu_in, float* y, hipStream_t st);
+// mod[l, i] = mtab[l, i] + e0[i]
+void launch_mod_add(const float* mtab, const float* e0, float* mod, int L, int n, hipStream_t st);
+void launch_rope_table(float2* tab, int n_pos, int pairs, float theta, hipStream_t st);
+void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
+// dst[s, head*d + c] (fp32) = src[head][row0 + s][c]
+template <typename T>
+void launch_gather_heads(const T* src, int64_t head_stride, int64_t row0, int64_t S, int h, int d,
+                         float* dst, hipStream_t st);
+// dst[s, head*d + c] (fp32) = vt[head][c][col0 + s]
+template <typename T>
+void launch_gather_vt(const T* vt, int64_t row_stride, int64_t col0, int64_t S, int h, int d,
+                      float* dst, hipStream_t st);
+
+// ---- gemm_f32.hip : C = A[M,K] * W[K,N] (+ epilogue), all row-major, fp32 FMA ---------------
+void launch_gemm_f32(const float* A, int64_t lda, const float* W, int64_t ldw, int64_t M, int64_t N,
+                     int64_t K, int epi, const EpiArgs& e, hipStream_t st);
+// ---- attn_f32.hip ----------------------------------------------------------------------------
+// q [h][*][d] rows q_row0.., k [h][*][d] rows k_row0.. (L rows), vt [h][d][*] cols k_row0.. ;
+// out[s, head*d + c], row stride ldo
+void launch_attn_f32(const float* q, int64_t q_head_stride, const float* k, int64_t k_head_stride,
+                     int64_t k_row0, const float* vt, int64_t vt_row_stride, int64_t S, int64_t L,
+                     int h, int d, float* out, int64_t ldo, hipStream_t st);
+
+// ---- gemm_bf16.hip : C = A[M,K] * Wt[N,K]^T (+ epilogue), bf16 MFMA, fp32 accumulate --------
+// A must be readable for roundup(M, 256) rows, Wt for roundup(N, 256) rows; K % 64 == 0.
+void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M,
+                      int64_t N, int64_t K, int epi, const EpiArgs& e, hipStream_t st);
+// ---- attn_bf16.hip : flash attention on MFMA, head_dim 64 or 128 ------------------------------
+// q readable for roundup(S, 256) rows per head; k rows / vt columns readable (finite in vt) up to
+// k_row0 + roundup(L, 64).
+void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
+                      int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
+                      int h, int d, bf16_t* out, int64_t ldo, hipStream_t st);

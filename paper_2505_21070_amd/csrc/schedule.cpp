@@ -1,0 +1,60 @@
+// Host-side queue schedule of block-wise denoising and the paper's bubble-ratio closed forms.
+#include "../../include/dualparal.h"
+
+int dp_set_error(int code, const char* msg);   // defined next to dp_last_error
+
+// Sec. 3.1: block b (video order, 1-based) enters the queue's tail at diffusion step b at level T;
+// every step each queued block is processed once and drops one level; a block leaves after its
+// level-1 pass, so at step s the queue holds the blocks with 1 <= T - (s - b) <= T.  Sec. 3.2: a
+// block reuses the K/V of the block processed just before it in the same step.  Sec. 3.3: the first
+// block may be longer.
+extern "C" int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry* out, int64_t capacity,
+                                     int64_t* n_written) {
+  if (!cfg || !n_written) return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: null pointer");
+  if (cfg->T < 1 || cfg->block_num < 1 || cfg->num_b < 1 || cfg->num_c < 0 || cfg->first_block_frames < 0)
+    return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: non-positive size");
+  if (cfg->order != DP_ORDER_REVERSE && cfg->order != DP_ORDER_SEQUENTIAL)
+    return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: unknown order");
+  const int64_t total = (int64_t)cfg->T * cfg->block_num;
+  *n_written = total;
+  if (capacity < total || !out) return dp_set_error(DP_ENOMEM, "dp_blockwise_schedule: capacity too small");
+  const int32_t T = cfg->T, B = cfg->block_num, half = cfg->num_c / 2;
+  const int32_t first = cfg->first_block_frames > 0 ? cfg->first_block_frames : cfg->num_b;
+  auto frames_of = [&](int32_t b) { return b == 1 ? first : cfg->num_b; };
+  auto start_of = [&](int32_t b) { return b == 1 ? 0 : first + (b - 2) * cfg->num_b; };
+  int64_t n = 0;
+  for (int32_t step = 1; step <= T + B - 1; ++step) {
+    int32_t lo = step - T + 1; if (lo < 1) lo = 1;        // cleanest block still queued (head)
+    int32_t hi = step < B ? step : B;                     // newest block (tail)
+    const bool rev = cfg->order == DP_ORDER_REVERSE;
+    int32_t prev = 0;
+    for (int32_t i = 0; i <= hi - lo; ++i) {
+      const int32_t b = rev ? hi - i : lo + i;
+      dp_sched_entry e;
+      e.step = step; e.block = b; e.level = T - (step - b);
+      e.timestep = cfg->t_max * (float)e.level / (float)T;
+      e.frame0 = start_of(b); e.n_frames = frames_of(b);
+      e.cache_block = 0; e.cache_first = 0; e.cache_frames = 0;
+      if (prev != 0 && half > 0) {
+        const int32_t pf = frames_of(prev);
+        e.cache_block = prev;
+        e.cache_frames = half < pf ? half : pf;
+        e.cache_first = rev ? 0 : pf - e.cache_frames;    // the neighbour's frames that touch block b
+      }
+      out[n++] = e;
+      prev = b;
+    }
+  }
+  return DP_OK;
+}
+
+// Eq. 3 (N <= Block_num), Eq. 4 (N > Block_num), Eq. 5 (sequential order), as printed.
+extern "C" double dp_bubble_ratio(int32_t N, int32_t T, int32_t block_num, int32_t order) {
+  if (N < 1 || T < 1 || block_num < 1) return -1.0;
+  double bubble;
+  if (order == DP_ORDER_SEQUENTIAL) bubble = (double)N * N - 1.0;
+  else if (order != DP_ORDER_REVERSE) return -1.0;
+  else if (N <= block_num) bubble = (double)N * N - N - 1.0;
+  else bubble = (double)block_num * (N - T) + (double)N * (T - 2) + 1.0;
+  return bubble / (bubble + (double)T * block_num);
+}

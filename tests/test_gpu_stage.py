@@ -1,0 +1,177 @@
+"""GPU parity: libdualparal (through its C ABI) against the CPU oracle, element by element, on the same
+seeded inputs.  Covers both storage types, the cache in both geometries, empty/cleared cache, ragged
+token counts, branch outputs (so that small gates cannot hide a broken branch) and the stage split."""
+import numpy as np
+import pytest
+import torch
+
+from harness import check, gpu_stage, oracle_stage, to_dev, to_np
+from paper_2505_21070_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+T_NB, T_CUR = 625.0, 500.0
+
+
+def run_pair(name, seed, strong_gate, cache_mode, report=None):
+    """Neighbour block -> cache hand-over -> current block, on both sides; compares everything visible."""
+    cfg, w, text, blocks = synth.make_case(name, seed=seed, strong_gate=strong_gate)
+    dt = cfg["dtype"]
+    nf, nc = cfg["block_frames"], cfg["cache_frames"]
+    g = gpu_stage(cfg, w, text, debug_taps=1, max_abs_frames=64)
+    o = oracle_stage(cfg, w, text)
+    if cache_mode == "later":      # the paper's geometry: the neighbour is the later block, its first frames touch us
+        f_nb, f_cur, first = nf, 0, 0
+    elif cache_mode == "earlier":  # neighbour precedes the block: its last frames touch us
+        f_nb, f_cur, first = 0, nf, nf - nc
+    else:
+        f_nb, f_cur, first = nf, 0, 0
+    y_nb = g.forward(to_dev(blocks[0], cfg), nf, f_nb, T_NB)
+    r_nb = o.forward(blocks[0].numpy(), nf, f_nb, T_NB)
+    check(f"{name}/nb/x_out", to_np(y_nb), r_nb, dt, report)
+    if cache_mode != "none":
+        g.cache_update(first, nc)
+        o.cache_update(first, nc)
+        for li in range(cfg["n_layers"]):
+            check(f"{name}/cache_k{li}", to_np(g.peek("cache_k", li)), o.cache[li][0], dt, report)
+            check(f"{name}/cache_v{li}", to_np(g.peek("cache_v", li)), o.cache[li][1], dt, report)
+    taps = []
+    x = to_dev(blocks[1], cfg)
+    y = g.forward(x, nf, f_cur, T_CUR)
+    r = o.forward(blocks[1].numpy(), nf, f_cur, T_CUR, taps)
+    last = taps[-1]
+    li = cfg["n_layers"] - 1
+    check(f"{name}/x_out", to_np(y), r, dt, report)
+    xres = to_np(g.peek("x_res", li))     # residual stream before the final rounding to the storage type
+    check(f"{name}/x_res", xres, r, dt, report)
+    check(f"{name}/delta", xres - blocks[1].numpy().astype(np.float64), r - blocks[1].numpy(), dt, report)
+    check(f"{name}/k", to_np(g.peek("k", li)), last["k"], dt, report)
+    check(f"{name}/v", to_np(g.peek("v", li)), last["v"], dt, report)
+    check(f"{name}/attn", to_np(g.peek("attn", li)), last["attn"], dt, report)
+    check(f"{name}/cross_attn", to_np(g.peek("cross_attn", li)), last["cattn"], dt, report)
+    check(f"{name}/x_self", to_np(g.peek("x_self", li)), last["x_self"], dt, report)
+    check(f"{name}/x_cross", to_np(g.peek("x_cross", li)), last["x_cross"], dt, report)
+    check(f"{name}/ffn_branch", xres - to_np(g.peek("x_cross", li)), r - last["x_cross"], dt, report)
+    return g, o, (cfg, w, text, blocks), (y, r)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("strong_gate", [False, True])
+def test_tiny_fp32_stage(seed, strong_gate):
+    rep = {}
+    run_pair("tiny", seed, strong_gate, "later", rep)
+    worst = max(v["max_abs"] for v in rep.values())
+    print(f"tiny fp32 seed {seed} strong_gate {strong_gate}: worst max_abs {worst:.3e}")
+
+
+@pytest.mark.parametrize("name", ["tiny_bf16", "small_bf16"])
+@pytest.mark.parametrize("strong_gate", [False, True])
+def test_small_bf16_stage(name, strong_gate):
+    rep = {}
+    run_pair(name, 0, strong_gate, "later", rep)
+    print({k: f"{v['rel_l2']:.2e}" for k, v in rep.items() if "cache" not in k})
+
+
+@pytest.mark.parametrize("name", ["tiny", "small_bf16"])
+def test_cache_before_block_and_no_cache(name):
+    run_pair(name, 1, True, "earlier")
+    run_pair(name, 1, True, "none")
+
+
+@pytest.mark.parametrize("name", ["tiny", "small_bf16"])
+def test_cleared_cache_equals_empty_and_inplace_output(name):
+    cfg, w, text, blocks = synth.make_case(name, seed=3, strong_gate=True)
+    nf, nc = cfg["block_frames"], cfg["cache_frames"]
+    g = gpu_stage(cfg, w, text)
+    x = to_dev(blocks[1], cfg)
+    a = g.forward(x, nf, 0, T_CUR).clone()
+    g.cache_update(0, nc)
+    b = g.forward(x, nf, 0, T_CUR).clone()
+    assert (a != b).any()
+    g.cache_update(0, 0)
+    c = g.forward(x, nf, 0, T_CUR)
+    assert torch.equal(a, c)
+    xi = x.clone()
+    g.forward(xi, nf, 0, T_CUR, out=xi)          # x_out aliases x_in
+    assert torch.equal(xi, a)
+
+
+def test_shorter_block_after_longer_and_partial_cache():
+    """A longer first block followed by shorter ones (stale rows beyond the block must not leak), and a
+    cache smaller than its maximum."""
+    cfg, w, text, _ = synth.make_case("small_bf16", seed=4, strong_gate=True)
+    g = gpu_stage(cfg, w, text, max_block_frames=4, max_cache_frames=2, max_abs_frames=32)
+    o = oracle_stage(cfg, w, text)
+    gen = torch.Generator().manual_seed(11)
+    xa, xb = synth.make_block(cfg, 4, gen), synth.make_block(cfg, 2, gen)
+    g.forward(to_dev(xa, cfg), 4, 2, 700.0); o.forward(xa.numpy(), 4, 2, 700.0)
+    g.cache_update(0, 1); o.cache_update(0, 1)
+    y = g.forward(to_dev(xb, cfg), 2, 0, 600.0); r = o.forward(xb.numpy(), 2, 0, 600.0)
+    check("short/x_out", to_np(y), r, "bf16")
+    check("short/delta", to_np(g.peek("x_res", 1)) - xb.numpy(), r - xb.numpy(), "bf16")
+
+
+@pytest.mark.parametrize("name", ["tiny", "tiny_bf16"])
+def test_stage_split_chains(name):
+    """Eq. 1: two one-layer stages chained through x_out -> x_in equal the two-layer stage."""
+    cfg, w, text, blocks = synth.make_case(name, seed=5, strong_gate=True)
+    nf, nc = cfg["block_frames"], cfg["cache_frames"]
+    whole = gpu_stage(cfg, w, text)
+    halves = [gpu_stage(dict(cfg, n_layers=1), {"stage": w["stage"], "layers": [w["layers"][i]]}, text) for i in range(2)]
+    def run(stages, x, f0, t):
+        for s in stages:
+            x = s.forward(x, nf, f0, t)
+        return x
+    run([whole], to_dev(blocks[0], cfg), nf, T_NB); whole.cache_update(0, nc)
+    run(halves, to_dev(blocks[0], cfg), nf, T_NB); [s.cache_update(0, nc) for s in halves]
+    a = run([whole], to_dev(blocks[1], cfg), 0, T_CUR)
+    b = run(halves, to_dev(blocks[1], cfg), 0, T_CUR)
+    if cfg["dtype"] == "f32":
+        assert torch.equal(a, b)
+    else:   # the hand-over between stages rounds the fp32 residual stream to bf16 once more
+        check("split", to_np(b), to_np(a), "bf16")
+
+
+def test_queue_sweep_matches_oracle():
+    """Block queue of Sec. 3.1 on a tiny model: 4 blocks, T = 4, tail-to-head, each block reading the cache
+    of the block processed just before it; every pass compared with the oracle."""
+    from paper_2505_21070_amd import binding as B
+    cfg, w, text, _ = synth.make_case("tiny", seed=6, strong_gate=True)
+    nb, T, num_b, num_c = 4, 4, cfg["block_frames"], 2 * cfg["cache_frames"]
+    gen = torch.Generator().manual_seed(7)
+    xs = synth.noise_pool_blocks(cfg, nb, num_b + num_c // 2, gen)
+    g = gpu_stage(cfg, w, text, max_abs_frames=nb * num_b)
+    o = oracle_stage(cfg, w, text)
+    sched = B.blockwise_schedule(T, nb, num_b, num_c, 0, 1000.0, "reverse")
+    assert len(sched) == T * nb
+    for e in sched:
+        if e["cache_block"] == 0:
+            g.cache_update(0, 0); o.cache_update(0, 0)
+        x = xs[e["block"] - 1]
+        y = g.forward(to_dev(x, cfg), e["n_frames"], e["frame0"], e["timestep"])
+        r = o.forward(x.numpy(), e["n_frames"], e["frame0"], e["timestep"])
+        check(f"queue/step{e['step']}/block{e['block']}", to_np(y), r, "f32")
+        g.cache_update(0, num_c // 2); o.cache_update(0, num_c // 2)
+
+
+def test_error_paths_leave_gpu_alone():
+    from paper_2505_21070_amd import binding as B
+    cfg, w, text, blocks = synth.make_case("tiny", seed=0)
+    g = gpu_stage(cfg, w, text)
+    with pytest.raises(B.DualParalError) as ei:
+        g.cache_update(0, 1)                      # no forward yet
+    assert ei.value.code == B.DP_ESTATE
+    x = to_dev(blocks[0], cfg)
+    with pytest.raises(B.DualParalError) as ei:
+        B._check(B._lib.dp_stage_forward(g._h, x.data_ptr(), x.data_ptr(), 3, 0, 1.0, None), "dp_stage_forward")
+    assert ei.value.code == B.DP_EINVAL           # more frames than max_block_frames
+    g.forward(x, 2, 0, 1.0)
+    with pytest.raises(B.DualParalError) as ei:
+        g.cache_update(1, 2)                      # beyond the last block / above max_cache_frames
+    assert ei.value.code == B.DP_EINVAL
+    conf = B.make_config(cfg)
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    h = B.C.c_void_p()
+    sw = B.StageWeights()
+    rc = B._lib.dp_stage_init(B.C.byref(conf), B.C.byref(sw), x.data_ptr(), ws.data_ptr(), 1024, None, B.C.byref(h))
+    assert rc == B.DP_EINVAL and not h.value      # null weights

@@ -1,0 +1,79 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, and its host-side
+entry points (schedule, bubble ratio, argument validation) behave.  No kernel runs here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.schedule import blockwise_schedule as oracle_schedule
+from oracle.schedule import bubble_ratio_reverse, bubble_ratio_sequential
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    lib = os.path.join(ROOT, "paper_2505_21070_amd", "libdualparal.so")
+    if not os.path.exists(lib):
+        from paper_2505_21070_amd import build
+        build.build()
+    from paper_2505_21070_amd import binding
+    return binding
+
+
+def test_exports_every_declared_symbol(B):
+    header = open(os.path.join(ROOT, "include", "dualparal.h")).read()
+    names = set(re.findall(r"\b(dp_[a-z_]+)\s*\(", header))
+    assert {"dp_stage_init", "dp_cache_update", "dp_stage_forward", "dp_blockwise_schedule"} <= names
+    for n in sorted(names):
+        assert hasattr(B._lib, n), n
+
+
+@pytest.mark.parametrize("args", [(8, 8, 4, 4, 0), (50, 4, 8, 8, 0), (4, 3, 4, 2, 5), (3, 1, 4, 4, 0), (5, 7, 4, 0, 0)])
+@pytest.mark.parametrize("order", ["reverse", "sequential"])
+def test_schedule_matches_oracle(B, args, order):
+    got = B.blockwise_schedule(*args, 1000.0, order)
+    ref = oracle_schedule(args[0], args[1], args[2], args[3], args[4] or None, 1000.0, order)
+    assert len(got) == len(ref) == args[0] * args[1]
+    for g, r in zip(got, ref):
+        for k, v in r.items():
+            assert g[k] == (np.float32(v) if k == "timestep" else v), (k, g, r)
+
+
+def test_schedule_capacity_and_bad_input(B):
+    cfg = B.SchedConfig(4, 3, 4, 4, 0, 0, 1000.0)
+    n = C.c_int64()
+    arr = (B.SchedEntry * 5)()
+    assert B._lib.dp_blockwise_schedule(C.byref(cfg), arr, 5, C.byref(n)) == B.DP_ENOMEM and n.value == 12
+    assert "capacity" in B.last_error()
+    bad = B.SchedConfig(0, 3, 4, 4, 0, 0, 1000.0)
+    assert B._lib.dp_blockwise_schedule(C.byref(bad), arr, 5, C.byref(n)) == B.DP_EINVAL
+    assert B._lib.dp_blockwise_schedule(None, arr, 5, C.byref(n)) == B.DP_EINVAL
+
+
+def test_bubble_ratio_matches_oracle_and_paper(B):
+    assert B.bubble_ratio(4, 50, 4) == pytest.approx(11 / 211)
+    for N, T, Bn in [(4, 50, 4), (8, 50, 64), (4, 50, 3), (2, 8, 8)]:
+        assert B.bubble_ratio(N, T, Bn) == pytest.approx(bubble_ratio_reverse(N, T, Bn))
+        assert B.bubble_ratio(N, T, Bn, "sequential") == pytest.approx(bubble_ratio_sequential(N, T, Bn))
+    assert B.bubble_ratio(0, 50, 4) == -1.0
+
+
+def test_config_validation_without_gpu(B):
+    from paper_2505_21070_amd import synth
+    good = B.make_config(synth.stage_config("wan1p3b_stage"))
+    nbytes = B.workspace_bytes(good)
+    assert 1 << 28 < nbytes < 1 << 32                     # a few hundred MB .. GBs for 4 Wan-1.3B layers
+    for field, value in [("head_dim", 96), ("n_heads", 11), ("dtype", 7), ("freq_dim", 255), ("tok_w", 51)]:
+        c = B.make_config(synth.stage_config("wan1p3b_stage"))
+        setattr(c, field, value)
+        assert B.workspace_bytes(c) == 0, field
+        assert B.last_error()
+    h = C.c_void_p(1)
+    assert B._lib.dp_stage_init(C.byref(good), None, None, None, 0, None, C.byref(h)) == B.DP_EINVAL
+    assert not h.value
+    assert B._lib.dp_stage_forward(None, None, None, 1, 0, 0.0, None) == B.DP_EINVAL
+    assert B._lib.dp_cache_update(None, 0, 1, None) == B.DP_EINVAL
+    B._lib.dp_stage_free(None)
