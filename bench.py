@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-wise denoising stage on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic frame block: dp_stage_forward (timestep
+modulation, then for every layer LayerNorm+modulate, QKV projection, q/k RMSNorm + 3D RoPE,
+self-attention over [cached K/V ; block], output projection, cross-attention, FFN) followed by
+dp_cache_update (feature-cache hand-over).  Inputs, weights and the primed cache are resident in HBM
+before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+PEAK_FP32_TFLOPS = 157.3      # fp32 vector
+PEAK_HBM_GBS = 8000.0         # HBM3E, published
+
+
+def class_work(cfg, S, Nc):
+    """Algorithmic work per launch of each kernel class: (flops, bytes).  bytes only for the HBM-bound ones."""
+    D, F, Lt = cfg["dim"], cfg["ffn_dim"], cfg["text_len"]
+    E = 2 if cfg["dtype"] == "bf16" else 4
+    return {
+        "self_attn": (4.0 * S * (S + Nc) * D, None),
+        "cross_attn": (4.0 * S * Lt * D, None),
+        "qkv_gemm": (2.0 * S * D * 3 * D, None),
+        "oproj_gemm": (2.0 * S * D * D, None),
+        "cross_q_gemm": (2.0 * S * D * D, None),
+        "cross_o_gemm": (2.0 * S * D * D, None),
+        "ffn1_gemm": (2.0 * S * D * F, None),
+        "ffn2_gemm": (2.0 * S * F * D, None),
+        "ln": (None, S * D * (4 + E)),                       # fp32 residual in, storage type out
+        "cache_copy": (None, 2 * (2 * Nc * D) * E),          # K and V of the retained frames, read + write
+        "norm_rope": (None, None), "modulation": (None, None), "convert": (None, None),
+    }
+
+
+def cpu_baseline(cfg, weights, text, x_block, n_rows=96):
+    """The CPU oracle timed on a bounded sample of the same workload: layer 0 of the stage on one block,
+    keys/values for every token of the block (and a synthetic cache of the workload's size), the rest of
+    the layer for `n_rows` sampled query rows; extrapolated to all rows and all layers."""
+    import numpy as np
+    from oracle.stage import OracleStage, token_positions
+    from paper_2505_21070_amd import synth
+    one = dict(cfg, n_layers=1)
+    wn = synth.to_numpy(weights)
+    t0 = time.perf_counter()
+    st = OracleStage(one, {"stage": wn["stage"], "layers": wn["layers"][:1]}, text.numpy())
+    t_init = time.perf_counter() - t0
+    nf, tok = cfg["block_frames"], cfg["tok_h"] * cfg["tok_w"]
+    S, Nc = nf * tok, cfg["cache_frames"] * tok
+    x = x_block.numpy().astype(np.float64)
+    e0 = st.modulation(500.0)
+    pos = token_positions(nf, 0, cfg["tok_h"], cfg["tok_w"])
+    rng = np.random.default_rng(0)
+    cache = (rng.standard_normal((Nc, cfg["dim"])), rng.standard_normal((Nc, cfg["dim"])))
+    rows = np.sort(rng.choice(S, size=n_rows, replace=False))
+    # keys/values of every token: time them alone by asking for zero query rows ...
+    t0 = time.perf_counter()
+    st.layer(0, x, e0, pos, cache, rows=rows[:1])
+    t_kv1 = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    st.layer(0, x, e0, pos, cache, rows=rows)
+    t_all = time.perf_counter() - t0
+    per_row = max(t_all - t_kv1, 1e-9) / (n_rows - 1)
+    t_layer = (t_kv1 - per_row) + per_row * S
+    t_stage = t_layer * cfg["n_layers"]
+    return {"value": S / t_stage, "unit": "tokens/s", "cores": int(os.environ.get("OMP_NUM_THREADS") or os.cpu_count()), "kind": "oracle",
+            "sample": f"fp64 oracle, layer 0 of {cfg['n_layers']}: K/V for all {S} tokens + {n_rows} sampled query rows "
+                      f"over {S + Nc} keys, {t_kv1 + t_all:.1f} s measured (+{t_init:.1f} s text side), "
+                      f"extrapolated to {S} rows x {cfg['n_layers']} layers = {t_stage:.0f} s per step"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="wan1p3b_stage")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="print the per-class time table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the stage has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    from paper_2505_21070_amd import binding as B
+    from paper_2505_21070_amd import synth
+
+    torch.cuda.set_device(0)
+    cfg, weights, text, blocks = synth.make_case(args.workload, seed=0, n_blocks=2)
+    nf, nc, tok = cfg["block_frames"], cfg["cache_frames"], cfg["tok_h"] * cfg["tok_w"]
+    S, Nc = nf * tok, nc * tok
+    td = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    conf = B.make_config(cfg, max_abs_frames=64)
+    stage = B.Stage(conf, B.weights_to_device(weights, cfg["dtype"]), text.to("cuda", td).contiguous())
+    x_nb, x_cur = (b.to("cuda", td).contiguous() for b in blocks)
+    out = torch.empty_like(x_cur)
+    # prime the cache the way the queue does: the neighbour (later, noisier) block runs first and hands
+    # its first cache_frames frames over
+    stage.forward(x_nb, nf, nf, 625.0, out=out)
+    stage.cache_update(0, nc)
+    torch.cuda.synchronize()
+
+    def step():
+        stage.forward(x_cur, nf, 0, 500.0, out=out)
+        stage.cache_update(0, nc)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # per-class breakdown (outside the timed region) to find the dominant kernel
+    work = class_work(cfg, S, Nc)
+    stage.profile_begin("all")
+    nb = max(2, min(5, args.steps))
+    for _ in range(nb):
+        step()
+    prof = stage.profile_end()
+    total_ms = sum(v[0] for v in prof.values())
+    dominant = max(prof, key=lambda k: prof[k][0])
+    breakdown = {}
+    for k, (ms, n) in sorted(prof.items(), key=lambda kv: -kv[1][0]):
+        fl, by = work[k]
+        ent = {"ms_per_launch": ms / n, "share": ms / total_ms}
+        if fl:
+            ent["tflops"] = fl / (ms / n * 1e-3) / 1e12
+        if by:
+            ent["gbs"] = by / (ms / n * 1e-3) / 1e9
+        breakdown[k] = ent
+    if args.breakdown:
+        for k, e in breakdown.items():
+            print(f"  {k:14s} {e['ms_per_launch']*1e3:9.1f} us/launch  {100*e['share']:5.1f} %"
+                  + (f"  {e['tflops']:8.1f} TFLOP/s" if "tflops" in e else "")
+                  + (f"  {e['gbs']:8.1f} GB/s" if "gbs" in e else ""), file=sys.stderr)
+    mf_classes = ("self_attn", "cross_attn", "ffn1_gemm", "ffn2_gemm")
+    mf_flops = sum(work[k][0] * prof[k][1] for k in mf_classes if k in prof)
+    mf_ms = sum(prof[k][0] for k in mf_classes if k in prof)
+    gemm_classes = [k for k in prof if work[k][0]]
+    all_flops = sum(work[k][0] * prof[k][1] for k in gemm_classes)
+    all_ms = sum(prof[k][0] for k in gemm_classes)
+
+    # timed region: K steps, HIP events only around the dominant kernel's launches
+    stage.profile_begin([dominant])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_n = stage.profile_end()[dominant]
+    assert torch.isfinite(out.float()).all()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    fl, by = work[dominant]
+    if fl:
+        peak = PEAK_BF16_TFLOPS if cfg["dtype"] == "bf16" else PEAK_FP32_TFLOPS
+        achieved = fl / (dom_ms / dom_n * 1e-3) / 1e12
+        roof = {"kernel": dominant, "bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "achieved": achieved,
+                "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "avg_launch_ms": dom_ms / dom_n, "launches": dom_n}
+    else:
+        achieved = by / (dom_ms / dom_n * 1e-3) / 1e9
+        roof = {"kernel": dominant, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": achieved / PEAK_HBM_GBS, "traffic": None, "avg_launch_ms": dom_ms / dom_n, "launches": dom_n}
+    res = {
+        "metric": "latent tokens/sec per DiT stage (cached block); attn+FFN TFLOP/s vs bf16 MFMA peak",
+        "value": S / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "layers": cfg["n_layers"], "dim": cfg["dim"], "heads": cfg["n_heads"],
+                   "head_dim": cfg["head_dim"], "ffn_dim": cfg["ffn_dim"], "block_tokens": S, "cached_tokens": Nc,
+                   "text_tokens": cfg["text_len"], "step": "dp_stage_forward + dp_cache_update"},
+        "roofline": roof,
+        "attn_ffn_tflops": mf_flops / (mf_ms * 1e-3) / 1e12 if mf_ms else None,
+        "attn_ffn_frac_of_bf16_peak": mf_flops / (mf_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if mf_ms else None,
+        "all_gemm_attn_tflops": all_flops / (all_ms * 1e-3) / 1e12 if all_ms else None,
+        "breakdown": breakdown,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg, weights, text, blocks[1])
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

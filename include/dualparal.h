@@ -170,6 +170,21 @@ enum { DP_PEEK_K = 0, DP_PEEK_V = 1, DP_PEEK_CACHE_K = 2, DP_PEEK_CACHE_V = 3, D
 int dp_stage_peek(dp_stage_t* stage, int32_t what, int32_t layer, float* dst, int64_t capacity,
                   int64_t* rows, void* hip_stream);
 
+/* Measurement hook: per-kernel-class GPU time from HIP events recorded on the caller's stream around
+ * the launches of the selected classes.  dp_stage_profile_begin(mask) starts collecting for the classes
+ * whose bit (1 << DP_PROF_*) is set (mask 0 stops collecting); dp_stage_profile_end waits for the
+ * recorded events and writes, for each of the DP_PROF_COUNT classes, the summed milliseconds and the
+ * number of launches into two host arrays, then stops collecting.  At most 16384 launches are recorded
+ * per begin/end pair; later ones are not timed.  Events are host-side objects; no device memory is
+ * allocated.  Errors: DP_EINVAL, DP_EHIP. */
+enum { DP_PROF_LN = 0, DP_PROF_QKV_GEMM = 1, DP_PROF_NORM_ROPE = 2, DP_PROF_SELF_ATTN = 3,
+       DP_PROF_OPROJ_GEMM = 4, DP_PROF_CROSS_Q_GEMM = 5, DP_PROF_CROSS_ATTN = 6, DP_PROF_CROSS_O_GEMM = 7,
+       DP_PROF_FFN1_GEMM = 8, DP_PROF_FFN2_GEMM = 9, DP_PROF_CACHE_COPY = 10, DP_PROF_MODULATION = 11,
+       DP_PROF_CONVERT = 12, DP_PROF_COUNT = 13 };
+int dp_stage_profile_begin(dp_stage_t* stage, uint32_t class_mask);
+int dp_stage_profile_end(dp_stage_t* stage, double* ms /* host [DP_PROF_COUNT] */,
+                         int64_t* launches /* host [DP_PROF_COUNT] */);
+
 /* Releases the host-side handle (device memory belongs to the caller).  NULL is allowed. */
 void dp_stage_free(dp_stage_t* stage);
 

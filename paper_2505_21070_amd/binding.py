@@ -68,6 +68,12 @@ _lib.dp_bubble_ratio.restype = C.c_double
 _lib.dp_bubble_ratio.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32]
 _lib.dp_stage_peek.restype = C.c_int
 _lib.dp_stage_peek.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.POINTER(C.c_int64), C.c_void_p]
+PROF = ("ln", "qkv_gemm", "norm_rope", "self_attn", "oproj_gemm", "cross_q_gemm", "cross_attn", "cross_o_gemm",
+        "ffn1_gemm", "ffn2_gemm", "cache_copy", "modulation", "convert")
+_lib.dp_stage_profile_begin.restype = C.c_int
+_lib.dp_stage_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
+_lib.dp_stage_profile_end.restype = C.c_int
+_lib.dp_stage_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 _lib.dp_stage_free.restype = None
 _lib.dp_stage_free.argtypes = [C.c_void_p]
 _lib.dp_last_error.restype = C.c_char_p
@@ -176,6 +182,21 @@ class Stage:
         _check(_lib.dp_stage_peek(self._h, PEEK[what], layer, buf.data_ptr(), buf.numel(), C.byref(rows),
                                   _stream_handle(stream)), "dp_stage_peek")
         return buf[: rows.value]
+
+    def profile_begin(self, classes):
+        """classes: iterable of names from PROF (or "all")."""
+        names = PROF if classes == "all" else classes
+        mask = 0
+        for n in names:
+            mask |= 1 << PROF.index(n)
+        _check(_lib.dp_stage_profile_begin(self._h, mask), "dp_stage_profile_begin")
+
+    def profile_end(self):
+        """{class: (total_ms, launches)} for the classes that were launched."""
+        ms = (C.c_double * len(PROF))()
+        n = (C.c_int64 * len(PROF))()
+        _check(_lib.dp_stage_profile_end(self._h, ms, n), "dp_stage_profile_end")
+        return {PROF[i]: (ms[i], n[i]) for i in range(len(PROF)) if n[i] > 0}
 
     def close(self):
         if self._h is not None:

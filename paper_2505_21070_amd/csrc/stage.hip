@@ -30,7 +30,29 @@ struct LayerMem {
   void *wqkv_t, *bqkv, *wo_t, *cwq_t, *cwo_t, *w1_t, *w2_t;   // bf16 path: weights as [out(pad 256), in]
 };
 
+struct Profiler {
+  uint32_t mask = 0;
+  std::vector<hipEvent_t> ev;     // pairs: (before, after)
+  std::vector<int> cls;
+  size_t used = 0;
+  bool on(int c) const { return (mask >> c) & 1u; }
+  bool begin(int c, hipStream_t st) {
+    if (!on(c) || used + 2 > ev.size()) return false;
+    (void)hipEventRecord(ev[used], st);
+    return true;
+  }
+  void end(int c, hipStream_t st) {
+    (void)hipEventRecord(ev[used + 1], st);
+    cls.push_back(c);
+    used += 2;
+  }
+  ~Profiler() { for (hipEvent_t e : ev) (void)hipEventDestroy(e); }
+};
+// times the launches in the statement block when class `c` is being profiled
+#define PROF(c, ...) do { const bool _p = s->prof.begin((c), st); __VA_ARGS__; if (_p) s->prof.end((c), st); } while (0)
+
 struct dp_stage {
+  Profiler prof;
   dp_stage_config cfg;
   dp_stage_weights w;
   std::vector<dp_layer_weights> lw;
@@ -284,48 +306,55 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
   const int64_t D = c.dim, F = c.ffn_dim, S = s->tok * n_frames;
   const int h = c.n_heads, d = c.head_dim;
   constexpr bool bf = sizeof(T) == 2;
-  launch_to_f32<T>((const T*)x_in, s->xres, S * D, st);
+  PROF(DP_PROF_CONVERT, launch_to_f32<T>((const T*)x_in, s->xres, S * D, st));
   // adaLN modulation: sinusoidal features -> two-layer MLP (SiLU) -> SiLU -> 6*dim head, plus each layer's table
-  launch_sinusoid(t, c.freq_dim, s->tau, st);
-  launch_gemv<T>(s->tau, c.freq_dim, (const T*)s->w.wt1, (const T*)s->w.bt1, (int)D, 0, s->e1, st);
-  launch_gemv<T>(s->e1, (int)D, (const T*)s->w.wt2, (const T*)s->w.bt2, (int)D, 1, s->e2, st);
-  launch_gemv<T>(s->e2, (int)D, (const T*)s->w.wm, (const T*)s->w.bm, (int)(6 * D), 1, s->e0, st);
-  launch_mod_add(s->mtab, s->e0, s->mod, c.n_layers, (int)(6 * D), st);
+  PROF(DP_PROF_MODULATION,
+       launch_sinusoid(t, c.freq_dim, s->tau, st);
+       launch_gemv<T>(s->tau, c.freq_dim, (const T*)s->w.wt1, (const T*)s->w.bt1, (int)D, 0, s->e1, st);
+       launch_gemv<T>(s->e1, (int)D, (const T*)s->w.wt2, (const T*)s->w.bt2, (int)D, 1, s->e2, st);
+       launch_gemv<T>(s->e2, (int)D, (const T*)s->w.wm, (const T*)s->w.bm, (int)(6 * D), 1, s->e0, st);
+       launch_mod_add(s->mtab, s->e0, s->mod, c.n_layers, (int)(6 * D), st));
   const int64_t kv_hs = s->Lpad * d;        // head stride of kbuf
   for (int l = 0; l < c.n_layers; ++l) {
     const dp_layer_weights& w = s->lw[(size_t)l]; LayerMem& m = s->lm[(size_t)l];
     const float* md = s->mod + (int64_t)l * 6 * D;
     const float *sh1 = md, *sc1 = md + D, *g1 = md + 2 * D, *sh2 = md + 3 * D, *sc2 = md + 4 * D, *g2 = md + 5 * D;
     // --- self-attention over [cached K/V ; this block]
-    launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, sc1, sh1, 1, st);
+    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, sc1, sh1, 1, st));
     if (bf) {
-      Path<T>::gemm(s->hbuf, D, nullptr, m.wqkv_t, S, 3 * D, D, EPI_STORE, epi_store(s->raw, 3 * D, m.bqkv), st);
+      PROF(DP_PROF_QKV_GEMM,
+           Path<T>::gemm(s->hbuf, D, nullptr, m.wqkv_t, S, 3 * D, D, EPI_STORE, epi_store(s->raw, 3 * D, m.bqkv), st));
     } else {
-      Path<T>::gemm(s->hbuf, D, w.wq, nullptr, S, D, D, EPI_STORE, epi_store(s->raw, 3 * D, w.bq), st);
-      Path<T>::gemm(s->hbuf, D, w.wk, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + D, 3 * D, w.bk), st);
-      Path<T>::gemm(s->hbuf, D, w.wv, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + 2 * D, 3 * D, w.bv), st);
+      PROF(DP_PROF_QKV_GEMM,
+           Path<T>::gemm(s->hbuf, D, w.wq, nullptr, S, D, D, EPI_STORE, epi_store(s->raw, 3 * D, w.bq), st);
+           Path<T>::gemm(s->hbuf, D, w.wk, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + D, 3 * D, w.bk), st);
+           Path<T>::gemm(s->hbuf, D, w.wv, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + 2 * D, 3 * D, w.bv), st));
     }
-    launch_norm_rope<T>((const T*)s->raw, 3 * D, 0, S, h, d, c.eps, m.gq, (T*)s->qbuf, s->Spad * d, 0, &s->rt, frame0, c.tok_h, c.tok_w, st);
-    launch_norm_rope<T>((const T*)s->raw, 3 * D, (int)D, S, h, d, c.eps, m.gk, (T*)m.kbuf, kv_hs, s->Ncmax, &s->rt, frame0, c.tok_h, c.tok_w, st);
-    launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, s->Ncmax, st);
-    Path<T>::attn(s->qbuf, s->Spad * d, m.kbuf, kv_hs, s->Ncmax - s->cache_len, m.vtbuf, s->Lpad, S,
-                  s->cache_len + S, h, d, s->attn_o, D, st);
+    PROF(DP_PROF_NORM_ROPE,
+         launch_norm_rope<T>((const T*)s->raw, 3 * D, 0, S, h, d, c.eps, m.gq, (T*)s->qbuf, s->Spad * d, 0, &s->rt, frame0, c.tok_h, c.tok_w, st);
+         launch_norm_rope<T>((const T*)s->raw, 3 * D, (int)D, S, h, d, c.eps, m.gk, (T*)m.kbuf, kv_hs, s->Ncmax, &s->rt, frame0, c.tok_h, c.tok_w, st);
+         launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, s->Ncmax, st));
+    PROF(DP_PROF_SELF_ATTN,
+         Path<T>::attn(s->qbuf, s->Spad * d, m.kbuf, kv_hs, s->Ncmax - s->cache_len, m.vtbuf, s->Lpad, S,
+                       s->cache_len + S, h, d, s->attn_o, D, st));
     if (s->tap_attn && l == c.n_layers - 1) launch_copy2d<T>((const T*)s->attn_o, 0, (T*)s->tap_attn, 0, 1, S * D, st);
-    Path<T>::gemm(s->attn_o, D, w.wo, m.wo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.bo, g1), st);
+    PROF(DP_PROF_OPROJ_GEMM, Path<T>::gemm(s->attn_o, D, w.wo, m.wo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.bo, g1), st));
     if (s->tap_xself && l == c.n_layers - 1) launch_copy2d<float>(s->xres, 0, s->tap_xself, 0, 1, S * D, st);
     // --- cross-attention to the text tokens
-    launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, m.ln3g, m.ln3b, 0, st);
-    Path<T>::gemm(s->hbuf, D, w.cwq, m.cwq_t, S, D, D, EPI_STORE, epi_store(s->raw, D, w.cbq), st);
-    launch_norm_rope<T>((const T*)s->raw, D, 0, S, h, d, c.eps, m.cgq, (T*)s->qbuf, s->Spad * d, 0, nullptr, 0, 1, 1, st);
-    Path<T>::attn(s->qbuf, s->Spad * d, m.tk, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, st);
-    Path<T>::gemm(s->attn_o, D, w.cwo, m.cwo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.cbo, nullptr), st);
+    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, m.ln3g, m.ln3b, 0, st));
+    PROF(DP_PROF_CROSS_Q_GEMM, Path<T>::gemm(s->hbuf, D, w.cwq, m.cwq_t, S, D, D, EPI_STORE, epi_store(s->raw, D, w.cbq), st));
+    PROF(DP_PROF_NORM_ROPE,
+         launch_norm_rope<T>((const T*)s->raw, D, 0, S, h, d, c.eps, m.cgq, (T*)s->qbuf, s->Spad * d, 0, nullptr, 0, 1, 1, st));
+    PROF(DP_PROF_CROSS_ATTN,
+         Path<T>::attn(s->qbuf, s->Spad * d, m.tk, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, st));
+    PROF(DP_PROF_CROSS_O_GEMM, Path<T>::gemm(s->attn_o, D, w.cwo, m.cwo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.cbo, nullptr), st));
     if (s->tap_xcross && l == c.n_layers - 1) launch_copy2d<float>(s->xres, 0, s->tap_xcross, 0, 1, S * D, st);
     // --- FFN
-    launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, sc2, sh2, 1, st);
-    Path<T>::gemm(s->hbuf, D, w.w1, m.w1_t, S, F, D, EPI_GELU, epi_store(s->mid, F, w.b1), st);
-    Path<T>::gemm(s->mid, F, w.w2, m.w2_t, S, D, F, EPI_RESID, epi_resid(s->xres, D, w.b2, g2), st);
+    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, sc2, sh2, 1, st));
+    PROF(DP_PROF_FFN1_GEMM, Path<T>::gemm(s->hbuf, D, w.w1, m.w1_t, S, F, D, EPI_GELU, epi_store(s->mid, F, w.b1), st));
+    PROF(DP_PROF_FFN2_GEMM, Path<T>::gemm(s->mid, F, w.w2, m.w2_t, S, D, F, EPI_RESID, epi_resid(s->xres, D, w.b2, g2), st));
   }
-  launch_from_f32<T>(s->xres, (T*)x_out, S * D, st);
+  PROF(DP_PROF_CONVERT, launch_from_f32<T>(s->xres, (T*)x_out, S * D, st));
 }
 
 extern "C" int dp_stage_forward(dp_stage_t* s, const void* x_in, void* x_out, int32_t n_frames, int32_t frame0,
@@ -353,8 +382,9 @@ static void cache_typed(dp_stage* s, int first, int n, hipStream_t st) {
   const int64_t len = s->tok * n, src0 = s->Ncmax + s->tok * first, dst0 = s->Ncmax - len;
   for (size_t l = 0; l < s->lm.size(); ++l) {
     T* kb = (T*)s->lm[l].kbuf; T* vb = (T*)s->lm[l].vtbuf;
-    launch_copy2d<T>(kb + src0 * d, s->Lpad * d, kb + dst0 * d, s->Lpad * d, h, len * d, st);
-    launch_copy2d<T>(vb + src0, s->Lpad, vb + dst0, s->Lpad, (int64_t)h * d, len, st);
+    PROF(DP_PROF_CACHE_COPY,
+         launch_copy2d<T>(kb + src0 * d, s->Lpad * d, kb + dst0 * d, s->Lpad * d, h, len * d, st);
+         launch_copy2d<T>(vb + src0, s->Lpad, vb + dst0, s->Lpad, (int64_t)h * d, len, st));
   }
 }
 
@@ -432,5 +462,38 @@ extern "C" int dp_stage_peek(dp_stage_t* s, int32_t what, int32_t layer, float* 
   if (rc != DP_OK) return rc;
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) return fail(DP_EHIP, "dp_stage_peek: %s", hipGetErrorString(err));
+  return DP_OK;
+}
+
+// ------------------------------------------------------------------------------------------ measurement hook
+extern "C" int dp_stage_profile_begin(dp_stage_t* s, uint32_t class_mask) {
+  if (!s) return fail(DP_EINVAL, "dp_stage_profile_begin: null stage");
+  Profiler& p = s->prof;
+  if (class_mask && p.ev.empty()) {
+    p.ev.resize(2 * 16384);
+    for (size_t i = 0; i < p.ev.size(); ++i) {
+      if (hipEventCreate(&p.ev[i]) != hipSuccess) {
+        for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(p.ev[j]);
+        p.ev.clear();
+        return fail(DP_EHIP, "dp_stage_profile_begin: hipEventCreate failed");
+      }
+    }
+  }
+  p.mask = class_mask; p.used = 0; p.cls.clear();
+  return DP_OK;
+}
+
+extern "C" int dp_stage_profile_end(dp_stage_t* s, double* ms, int64_t* launches) {
+  if (!s || !ms || !launches) return fail(DP_EINVAL, "dp_stage_profile_end: null pointer");
+  Profiler& p = s->prof;
+  for (int i = 0; i < DP_PROF_COUNT; ++i) { ms[i] = 0.0; launches[i] = 0; }
+  p.mask = 0;
+  for (size_t i = 0; i < p.cls.size(); ++i) {
+    if (hipEventSynchronize(p.ev[2 * i + 1]) != hipSuccess) return fail(DP_EHIP, "dp_stage_profile_end: hipEventSynchronize failed");
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, p.ev[2 * i], p.ev[2 * i + 1]) != hipSuccess) return fail(DP_EHIP, "dp_stage_profile_end: hipEventElapsedTime failed");
+    ms[p.cls[i]] += (double)t; launches[p.cls[i]] += 1;
+  }
+  p.used = 0; p.cls.clear();
   return DP_OK;
 }
