@@ -101,13 +101,12 @@ __global__ __launch_bounds__(256) void k_attn_bf16(const bf16_t* __restrict__ q,
   __syncthreads();
 
   for (int kt = 0; kt < NKT; ++kt) {
-    const bool more = kt + 1 < NKT;
-    if (more) {
+    // prefetch the next key tile (the last iteration re-reads its own tile; the copy is never used)
+    const int ktn = kt + 1 < NKT ? kt + 1 : kt;
 #pragma unroll
-      for (int i = 0; i < CK; ++i) rk[i] = gk[i][(int64_t)(kt + 1) * 64 * CR];   // 64 rows of CR chunks
+    for (int i = 0; i < CK; ++i) rk[i] = gk[i][(int64_t)ktn * 64 * CR];            // 64 rows of CR chunks
 #pragma unroll
-      for (int i = 0; i < CV; ++i) rv[i] = gv[i][(kt + 1) * 8];                    // 64 keys = 8 chunks
-    }
+    for (int i = 0; i < CV; ++i) rv[i] = gv[i][ktn * 8];                           // 64 keys = 8 chunks
     const uint4* buf = smem + (kt & 1) * STAGE;
 
     // S^T tiles: [2 key tiles of 32][QT query tiles]
@@ -189,7 +188,7 @@ __global__ __launch_bounds__(256) void k_attn_bf16(const bf16_t* __restrict__ q,
           oacc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pf[t][u4]), oacc[a][t], 0, 0, 0);
       }
     }
-    if (more) {
+    {
       uint4* nb = smem + ((kt + 1) & 1) * STAGE;
       uint2* n2 = (uint2*)nb;
 #pragma unroll

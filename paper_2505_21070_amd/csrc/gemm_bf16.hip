@@ -67,13 +67,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
 
   const int lr = lane & 31, lg = lane >> 5;
   for (int kt = 0; kt < KT; ++kt) {
-    const bool more = kt + 1 < KT;
-    if (more) {
+    // prefetch the next k-tile (the last iteration re-reads its own tile; the copy is never used)
+    const int ktn = kt + 1 < KT ? kt + 1 : kt;
 #pragma unroll
-      for (int i = 0; i < CA; ++i) ra[i] = ga[i][(kt + 1) * 8];     // 8 chunks = 64 bf16 along K
+    for (int i = 0; i < CA; ++i) ra[i] = ga[i][ktn * 8];            // 8 chunks = 64 bf16 along K
 #pragma unroll
-      for (int i = 0; i < CB; ++i) rb[i] = gb[i][(kt + 1) * 8];
-    }
+    for (int i = 0; i < CB; ++i) rb[i] = gb[i][ktn * 8];
     const uint4* buf = smem + (kt & 1) * STAGE;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -95,7 +94,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
-    if (more) {
+    {
       uint4* nb = smem + ((kt + 1) & 1) * STAGE;
 #pragma unroll
       for (int i = 0; i < CA; ++i) nb[sa[i]] = ra[i];
