@@ -2,220 +2,270 @@
 // contiguous key range [cached prefix ; current block] streamed from HBM through LDS tiles, with an
 // online softmax in fp32.  Used for self-attention (cache + block) and cross-attention (text keys).
 //
-// The scores are computed transposed, S^T = K * Q^T (keys are MFMA rows, queries MFMA columns): a
-// lane then owns one query column, so the softmax max/sum are reductions over the lane's own
+// Scores are computed transposed, S^T = K * Q^T (keys are MFMA rows, queries MFMA columns): a lane
+// then owns one query column, so the softmax maximum and sum are reductions over the lane's own
 // registers plus one exchange with lane ^ 32, and the fp32 S^T accumulators, once exponentiated and
-// rounded to bf16, ARE the B operand of the second product O^T = V^T * P^T (the k index of that
-// product is a fixed permutation of the keys, applied to V^T when it is written to LDS).
+// rounded to bf16, ARE the B operand of the second product O^T = V^T * P^T.  The rows of a K tile are
+// stored in a permuted order so that the eight accumulators a lane packs into one operand belong to
+// eight consecutive keys, which makes the matching V^T operand one plain 16-byte LDS read.
 //
-// Block: 4 wavefronts x (QT x 32) queries of one head; key tile 64; K tile [64][HD] and V^T tile
-// [HD][64] double-buffered in LDS; global loads for tile i+1 are in flight while tile i is used.
+// Q arrives pre-multiplied by log2(e)/sqrt(head_dim), so scores are base-2 logits.  The softmax reference
+// m of a query is folded into the accumulator that the score MFMAs start from (-m instead of 0), so the
+// matrix cores hand back s - m and the vector unit only has to exponentiate.  Fast pass: m is fixed once,
+// to the query's maximum over the first 32 keys of its key group, and never raised, so O^T needs no
+// rescaling and the loop body is straight-line code.  This is exact as long as nothing overflows: P (bf16)
+// and the fp32 sums have 8 exponent bits, so scores may exceed m by ~2^100 before anything is lost.  A
+// block whose row sums end up beyond 2^100 (or non-finite) is recomputed by the safe pass, the classical
+// online softmax that raises m whenever a tile exceeds it and rescales O^T.
+//
+// Work split: a block of 8 wavefronts owns 128 queries of one head; wavefront w handles query tile
+// w & 3 (32 queries) against key group w >> 2 (first / second half of the key tiles).  The two groups
+// stream their own K / V^T tiles (64 keys, double-buffered, loaded HBM -> LDS directly) and are merged
+// through LDS at the end.  Two wavefronts per SIMD hide each other's LDS and matrix-core latencies; the
+// key split halves the length of a block so that the tail of the grid wastes less of the machine.
+#include <type_traits>
+
 #include "kernels.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_void_t;
 
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
   f32x2 v = {a, b};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
+// acc + lo + hi of a packed bf16 pair
+__device__ __forceinline__ float add_pk_bf16(uint32_t pk, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+}
+// LDS has 64 four-byte banks: 16 lanes x 16 bytes are served per cycle.  XOR-swizzling the 16-byte chunk
+// index with the row spreads a column of chunks over all banks: rows of 256 bytes use row & 15, rows of
+// 128 bytes (two rows per bank sweep) use (row >> 1) & 7.
+template <int CR> __device__ __forceinline__ int kswz(int row) { return CR == 16 ? (row & 15) : ((row >> 1) & 7); }
+// tile row -> key held in that row: bits 2 and 3 of the row index are exchanged
+__device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
-template <int HD, int QT>
-__global__ __launch_bounds__(256) void k_attn_bf16(const bf16_t* __restrict__ q, int64_t q_head_stride,
+template <int HD>
+__global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q, int64_t q_head_stride,
                                                   const bf16_t* __restrict__ k, int64_t k_head_stride,
                                                   int64_t k_row0, const bf16_t* __restrict__ vt,
                                                   int64_t vt_row_stride, int64_t S, int64_t L,
-                                                  bf16_t* __restrict__ out, int64_t ldo, float sc2) {
+                                                  bf16_t* __restrict__ out, int64_t ldo) {
   constexpr int CR = HD / 8;                 // 16-byte chunks per K row
   constexpr int KS = HD / 16;                // MFMA k-steps over the head dim
   constexpr int DT = HD / 32;                // 32-row tiles of O^T
-  constexpr int KCH = 64 * CR;               // chunks in the K tile
-  constexpr int VCH = HD * 8;                // chunks in the V^T tile
-  constexpr int STAGE = KCH + VCH;
+  constexpr int KCH = 64 * CR;               // chunks in a K tile
+  constexpr int VCH = HD * 8;                // chunks in a V^T tile
+  constexpr int GCH = 2 * KCH + 2 * VCH;     // chunks per key group: K tiles 0/1, V^T tiles 0/1
   constexpr int CK = KCH / 256, CV = VCH / 256;
-  __shared__ uint4 smem[2 * STAGE];
+  extern __shared__ uint4 smem[];            // 2 * GCH chunks
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int qt = wave & 3, kg = wave >> 2;
   const int lr = lane & 31, lg = lane >> 5;
   const int head = blockIdx.y;
-  const int64_t q0 = ((int64_t)blockIdx.x * 4 + wave) * (QT * 32);
+  const int64_t q0 = (int64_t)blockIdx.x * 128 + qt * 32;
+  uint4* const kbuf = smem + kg * GCH;
+  uint4* const vbuf = kbuf + 2 * KCH;
+
+  // this wavefront's share of the key tiles
+  const int NKT = (int)((L + 63) / 64);
+  const int n0 = (NKT + 1) / 2;                       // tiles of group 0; also the trip count for everyone
+  const int first = kg ? n0 : 0, cnt = kg ? NKT - n0 : n0;
 
   // Q fragments stay in registers: B operand, column = query, 8 head-dim values per lane
-  bf16x8 qf[QT][KS];
+  bf16x8 qf[KS];
   {
-    const bf16_t* qh = q + (int64_t)head * q_head_stride;
+    const bf16_t* qh = q + (int64_t)head * q_head_stride + (q0 + lr) * HD + lg * 8;
 #pragma unroll
-    for (int t = 0; t < QT; ++t)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        qf[t][ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qh + (q0 + t * 32 + lr) * HD + ks * 16 + lg * 8));
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qh + ks * 16));
   }
-  const bf16_t* kh = k + (int64_t)head * k_head_stride + k_row0 * HD;
-  const bf16_t* vh = vt + (int64_t)head * HD * vt_row_stride + k_row0;
+  const bf16_t* kh = k + (int64_t)head * k_head_stride + (k_row0 + (int64_t)first * 64) * HD;
+  const bf16_t* vh = vt + (int64_t)head * HD * vt_row_stride + k_row0 + (int64_t)first * 64;
 
-  // global -> LDS assignment
-  const uint4* gk[CK]; int sk[CK];
+  // HBM -> LDS directly (no staging registers).  One wavefront instruction fills 64 consecutive
+  // 16-byte LDS slots, slot = base + lane; each lane fetches the chunk that belongs in its slot:
+  // K slot p holds chunk (p % CR) ^ kswz(row) of key swap23(row), row = p / CR;
+  // V^T slot p holds chunk (p % 8) ^ ((row >> 1) & 7) of channel row = p / 8.
+  int koff[CK], voff[CV];
 #pragma unroll
   for (int i = 0; i < CK; ++i) {
-    const int c = tid + i * 256, row = c / CR, ch = c % CR;
-    gk[i] = (const uint4*)(kh + (int64_t)row * HD + ch * 8);
-    sk[i] = row * CR + (ch ^ (row & (CR - 1)));
+    const int p = qt * (KCH / 4) + i * 64 + lane, row = p / CR, ch = (p % CR) ^ kswz<CR>(row);
+    koff[i] = swap23(row) * HD + ch * 8;
   }
-  const uint4* gv[CV]; int sv0[CV], sv1[CV];
 #pragma unroll
   for (int i = 0; i < CV; ++i) {
-    const int c = tid + i * 256, row = c >> 3, ch = c & 7;       // ch: 8 keys [8ch, 8ch+8)
-    gv[i] = (const uint4*)(vh + (int64_t)row * vt_row_stride + ch * 8);
-    // keys 8ch+0..3 -> chunk 2*(ch/2), half (ch&1); keys 8ch+4..7 -> chunk 2*(ch/2)+1, half (ch&1)
-    const int c0 = (ch & ~1), c1 = c0 + 1;
-    sv0[i] = (KCH + row * 8 + (c0 ^ (row & 7))) * 2 + (ch & 1);  // in 8-byte units
-    sv1[i] = (KCH + row * 8 + (c1 ^ (row & 7))) * 2 + (ch & 1);
+    const int p = qt * (VCH / 4) + i * 64 + lane, row = p >> 3, ch = (p & 7) ^ ((row >> 1) & 7);
+    voff[i] = row * (int)vt_row_stride + ch * 8;
+  }
+  auto load_tile = [&](int tile, int bufi) __attribute__((always_inline)) {
+    const bf16_t* ks_ = kh + (int64_t)tile * 64 * HD;
+    const bf16_t* vs_ = vh + (int64_t)tile * 64;
+#pragma unroll
+    for (int i = 0; i < CK; ++i)
+      __builtin_amdgcn_global_load_lds((glb_void_t*)(ks_ + koff[i]),
+                                       (lds_void_t*)(kbuf + bufi * KCH + qt * (KCH / 4) + i * 64), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < CV; ++i)
+      __builtin_amdgcn_global_load_lds((glb_void_t*)(vs_ + voff[i]),
+                                       (lds_void_t*)(vbuf + bufi * VCH + qt * (VCH / 4) + i * 64), 16, 0, 0);
+  };
+
+  f32x16 oacc[DT], negm;
+  float mrun, lsum;
+
+  // One pass over this wavefront's key tiles.  SAFE = false: fixed reference (see the file header).
+  // SAFE = true: classical online softmax, reference raised per 32-key half tile, O^T rescaled.
+  auto pass = [&](auto safe_tag) __attribute__((always_inline)) {
+    constexpr bool SAFE = decltype(safe_tag)::value;
+#pragma unroll
+    for (int a = 0; a < DT; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[a][r] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[r] = 0.f;
+    mrun = 0.f; lsum = 0.f;
+    bool fresh = true;                                  // SAFE: no key seen yet, mrun is a placeholder
+
+    if (cnt > 0) load_tile(0, 0);
+    __syncthreads();
+    if (!SAFE && cnt > 0) {
+      // reference = maximum over the first 32 keys (all valid: a group's first tile starts below L)
+      f32x16 s0;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int row = lr, ch = ks * 2 + lg;
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, kbuf[row * CR + (ch ^ kswz<CR>(row))]);
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? negm : s0, 0, 0, 0);
+      }
+      const int kv0 = (int)(L - (int64_t)first * 64);
+      float mx = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (swap23((r >> 2) * 8 + lg * 4 + (r & 3)) < kv0) mx = fmaxf(mx, s0[r]);
+      mrun = fmaxf(mx, __shfl_xor(mx, 32, 64));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) negm[r] = -mrun;
+    }
+
+    for (int kt = 0; kt < n0; ++kt) {
+      if (kt < cnt) {
+        // next tile into the other buffer (read last before the previous barrier); the tile past the
+        // end is the last one again and never used
+        load_tile(kt + 1 < cnt ? kt + 1 : cnt - 1, (kt + 1) & 1);
+        const uint4* kb = kbuf + (kt & 1) * KCH;
+        const uint4* vb = vbuf + (kt & 1) * VCH;
+        const int kvalid = (int)(L - (int64_t)(first + kt) * 64);     // < 64 only in the ragged last tile
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {                                  // two 32-key halves of the tile
+          // S^T - m : 32 keys x 32 queries, accumulation started from -m
+          f32x16 sacc;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const int row = a * 32 + lr, ch = ks * 2 + lg;
+            const bf16x8 kf = __builtin_bit_cast(bf16x8, kb[row * CR + (ch ^ kswz<CR>(row))]);
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? negm : sacc, 0, 0, 0);
+          }
+          // register r, lane group lg, is tile row a*32 + (r/4)*8 + lg*4 + (r%4), which holds key
+          // swap23(row); keys at or beyond L get -inf
+          if (kvalid < 64) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if (swap23(a * 32 + (r >> 2) * 8 + lg * 4 + (r & 3)) >= kvalid) sacc[r] = -INFINITY;
+          }
+          if constexpr (SAFE) {
+            float mx = sacc[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sacc[r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                    // maximum of this half relative to m
+            const float up = fresh ? mx : fmaxf(mx, 0.f);
+            const float alpha = fresh ? 0.f : __builtin_amdgcn_exp2f(-up);
+            mrun += up;
+            lsum *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+              for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { sacc[r] -= up; negm[r] = -mrun; }
+            fresh = false;
+          }
+          // P = 2^(s - m), packed to bf16 as the B operand of O^T += V^T P^T; row sums from the rounded values
+          uint4 pf[2];
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              w[j] = cvt_pk_bf16(__builtin_amdgcn_exp2f(sacc[u * 8 + 2 * j]), __builtin_amdgcn_exp2f(sacc[u * 8 + 2 * j + 1]));
+              lsum = add_pk_bf16(w[j], lsum);
+            }
+            pf[u] = make_uint4(w[0], w[1], w[2], w[3]);
+          }
+          // O^T += V^T * P^T : k-step u covers keys [a*32 + 16u, +16), lane group lg the lower/upper 8
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+              const int row = dt * 32 + lr, ch = (a * 2 + u) * 2 + lg;
+              const bf16x8 vf = __builtin_bit_cast(bf16x8, vb[row * 8 + (ch ^ ((row >> 1) & 7))]);
+              oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pf[u]), oacc[dt], 0, 0, 0);
+            }
+          }
+        }
+      }
+      __syncthreads();      // the next tile has landed and every wavefront is done with this one
+    }
+    return fresh;
+  };
+
+  pass(std::false_type{});
+  const bool empty = cnt == 0;                          // this key group has no tile (a single-tile key range)
+  float ltot = lsum + __shfl_xor(lsum, 32, 64);
+  if (__syncthreads_or(!empty && !(ltot <= 0x1p100f))) {  // overflow somewhere in the block: redo it safely
+    pass(std::true_type{});
+    ltot = lsum + __shfl_xor(lsum, 32, 64);
   }
 
-  f32x16 oacc[DT][QT];
+  // merge the two key groups through LDS (tile buffers are free now): group 1 publishes m, l, O^T
+  float* xch = (float*)smem;                           // [qt][DT*16 + 2][64 lanes]
+  float* mine = xch + (size_t)qt * (DT * 16 + 2) * 64 + lane;
+  if (kg == 1) {
+    mine[0] = empty ? -INFINITY : mrun;
+    mine[64] = ltot;
 #pragma unroll
-  for (int a = 0; a < DT; ++a)
+    for (int a = 0; a < DT; ++a)
 #pragma unroll
-    for (int t = 0; t < QT; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[a][t][r] = 0.f;
-  float mrun[QT], lsum[QT];
-#pragma unroll
-  for (int t = 0; t < QT; ++t) { mrun[t] = -INFINITY; lsum[t] = 0.f; }
-
-  const int NKT = (int)((L + 63) / 64);
-  uint4 rk[CK], rv[CV];
-#pragma unroll
-  for (int i = 0; i < CK; ++i) rk[i] = gk[i][0];
-#pragma unroll
-  for (int i = 0; i < CV; ++i) rv[i] = gv[i][0];
-  {
-    uint2* s2 = (uint2*)smem;
-#pragma unroll
-    for (int i = 0; i < CK; ++i) smem[sk[i]] = rk[i];
-#pragma unroll
-    for (int i = 0; i < CV; ++i) { s2[sv0[i]] = make_uint2(rv[i].x, rv[i].y); s2[sv1[i]] = make_uint2(rv[i].z, rv[i].w); }
+      for (int r = 0; r < 16; ++r) mine[(2 + a * 16 + r) * 64] = oacc[a][r];
   }
   __syncthreads();
-
-  for (int kt = 0; kt < NKT; ++kt) {
-    // prefetch the next key tile (the last iteration re-reads its own tile; the copy is never used)
-    const int ktn = kt + 1 < NKT ? kt + 1 : kt;
-#pragma unroll
-    for (int i = 0; i < CK; ++i) rk[i] = gk[i][(int64_t)ktn * 64 * CR];            // 64 rows of CR chunks
-#pragma unroll
-    for (int i = 0; i < CV; ++i) rv[i] = gv[i][ktn * 8];                           // 64 keys = 8 chunks
-    const uint4* buf = smem + (kt & 1) * STAGE;
-
-    // S^T tiles: [2 key tiles of 32][QT query tiles]
-    f32x16 sacc[2][QT];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int t = 0; t < QT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[a][t][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
-        const int row = a * 32 + lr, ch = ks * 2 + lg;
-        const bf16x8 kf = __builtin_bit_cast(bf16x8, buf[row * CR + (ch ^ (row & (CR - 1)))]);
-#pragma unroll
-        for (int t = 0; t < QT; ++t)
-          sacc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], sacc[a][t], 0, 0, 0);
-      }
-    }
-    // mask keys beyond L (last tile only): register r of tile a is key a*32 + (r/4)*8 + lg*4 + (r%4)
-    const int kvalid = (int)(L - (int64_t)kt * 64);
-    if (kvalid < 64) {
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = a * 32 + (r >> 2) * 8 + lg * 4 + (r & 3);
-          if (key >= kvalid) {
-#pragma unroll
-            for (int t = 0; t < QT; ++t) sacc[a][t][r] = -INFINITY;
-          }
-        }
-    }
-    // online softmax per query column; probabilities packed as the B operand of O^T += V^T P^T
-    uint4 pf[QT][4];
-#pragma unroll
-    for (int t = 0; t < QT; ++t) {
-      float mx = sacc[0][t][0];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[a][t][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mnew = fmaxf(mrun[t], mx * sc2);
-      const float alpha = __builtin_amdgcn_exp2f(mrun[t] - mnew);
-      mrun[t] = mnew;
-      float ps = 0.f;
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          float p[8];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            p[j] = __builtin_amdgcn_exp2f(fmaf(sacc[a][t][u * 8 + j], sc2, -mnew));
-            ps += p[j];
-          }
-          pf[t][a * 2 + u] = make_uint4(cvt_pk_bf16(p[0], p[1]), cvt_pk_bf16(p[2], p[3]),
-                                        cvt_pk_bf16(p[4], p[5]), cvt_pk_bf16(p[6], p[7]));
-        }
-      }
-      lsum[t] = lsum[t] * alpha + ps;
-#pragma unroll
-      for (int a = 0; a < DT; ++a)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[a][t][r] *= alpha;
-    }
-    // O^T += V^T * P^T
-#pragma unroll
-    for (int u4 = 0; u4 < 4; ++u4) {
-#pragma unroll
-      for (int a = 0; a < DT; ++a) {
-        const int row = a * 32 + lr, ch = u4 * 2 + lg;
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, buf[KCH + row * 8 + (ch ^ (row & 7))]);
-#pragma unroll
-        for (int t = 0; t < QT; ++t)
-          oacc[a][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pf[t][u4]), oacc[a][t], 0, 0, 0);
-      }
-    }
-    {
-      uint4* nb = smem + ((kt + 1) & 1) * STAGE;
-      uint2* n2 = (uint2*)nb;
-#pragma unroll
-      for (int i = 0; i < CK; ++i) nb[sk[i]] = rk[i];
-#pragma unroll
-      for (int i = 0; i < CV; ++i) { n2[sv0[i]] = make_uint2(rv[i].x, rv[i].y); n2[sv1[i]] = make_uint2(rv[i].z, rv[i].w); }
-    }
-    __syncthreads();
-  }
-
-  // O[q][head*HD + c] = O^T[c][q] / l ; lane holds 4 consecutive c per register quad
-#pragma unroll
-  for (int t = 0; t < QT; ++t) {
-    const int64_t qi = q0 + t * 32 + lr;
-    const float l = lsum[t] + __shfl_xor(lsum[t], 32, 64);
-    const float inv = 1.f / l;
+  if (kg == 0) {
+    const float m1 = mine[0], l1 = mine[64];
+    const float m0 = empty ? -INFINITY : mrun;
+    const float m = fmaxf(m0, m1);
+    const float a0 = __builtin_amdgcn_exp2f(m0 - m), a1 = __builtin_amdgcn_exp2f(m1 - m);   // 2^-inf = 0
+    const float inv = 1.f / (ltot * a0 + l1 * a1);
+    const float w0 = a0 * inv, w1 = a1 * inv;
+    const int64_t qi = q0 + lr;
     if (qi < S) {
+      // O[q][head*HD + c] = O^T[c][q] ; lane holds 4 consecutive c per register quad
       bf16_t* o = out + qi * ldo + (int64_t)head * HD;
 #pragma unroll
       for (int a = 0; a < DT; ++a)
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          const int c = a * 32 + g4 * 8 + lg * 4;
+          float v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) v[j] = oacc[a][g4 * 4 + j] * w0 + mine[(2 + a * 16 + g4 * 4 + j) * 64] * w1;
           uint2 pk;
-          pk.x = cvt_pk_bf16(oacc[a][t][g4 * 4 + 0] * inv, oacc[a][t][g4 * 4 + 1] * inv);
-          pk.y = cvt_pk_bf16(oacc[a][t][g4 * 4 + 2] * inv, oacc[a][t][g4 * 4 + 3] * inv);
-          *(uint2*)(o + c) = pk;
+          pk.x = cvt_pk_bf16(v[0], v[1]);
+          pk.y = cvt_pk_bf16(v[2], v[3]);
+          *(uint2*)(o + a * 32 + g4 * 8 + lg * 4) = pk;
         }
     }
   }
@@ -225,11 +275,15 @@ void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, i
                       int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
                       int h, int d, bf16_t* out, int64_t ldo, hipStream_t st) {
   if (S <= 0 || L <= 0) return;
-  const float sc2 = 1.4426950408889634f / sqrtf((float)d);
-  constexpr int QT = 2;
-  dim3 grid((unsigned)((S + 4 * QT * 32 - 1) / (4 * QT * 32)), (unsigned)h);
+  dim3 grid((unsigned)((S + 127) / 128), (unsigned)h);
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)k_attn_bf16<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16);
+    (void)hipFuncSetAttribute((const void*)k_attn_bf16<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (2 * 64 * 8 + 2 * 64 * 8) * 16);
+    attr_done = true;
+  }
   if (d == 128)
-    k_attn_bf16<128, QT><<<grid, 256, 0, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, sc2);
+    k_attn_bf16<128><<<grid, 512, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo);
   else
-    k_attn_bf16<64, QT><<<grid, 256, 0, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, sc2);
+    k_attn_bf16<64><<<grid, 512, 2 * (2 * 64 * 8 + 2 * 64 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo);
 }

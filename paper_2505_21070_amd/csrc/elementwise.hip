@@ -112,7 +112,7 @@ template void launch_ln_modulate<bf16_t>(const float*, bf16_t*, int64_t, int, fl
 // One block per token.  Each thread owns channel pairs (2p, 2p+1), p = tid, tid + 256, ...
 template <typename T>
 __global__ __launch_bounds__(256) void k_norm_rope(const T* __restrict__ src, int64_t ld, int col, int h,
-                                                   int d, float eps, const float* __restrict__ g,
+                                                   int d, float eps, const float* __restrict__ g, float out_scale,
                                                    T* __restrict__ dst, int64_t head_stride, int64_t row0,
                                                    RopeTables rt, int use_rope, int frame0, int tok_h,
                                                    int tok_w) {
@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void k_norm_rope(const T* __restrict__ src, in
   sq = wave_sum(sq);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
   __syncthreads();
-  const float r = rsqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)D + eps);
+  const float r = rsqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)D + eps) * out_scale;
   const int tok = tok_h * tok_w;
   const int f = frame0 + (int)(s / tok), rem = (int)(s % tok);
   const int y = rem / tok_w, x = rem % tok_w;
@@ -152,15 +152,15 @@ __global__ __launch_bounds__(256) void k_norm_rope(const T* __restrict__ src, in
 }
 template <typename T>
 void launch_norm_rope(const T* src, int64_t ld, int col, int64_t S, int h, int d, float eps,
-                      const float* g, T* dst, int64_t head_stride, int64_t row0,
+                      const float* g, float out_scale, T* dst, int64_t head_stride, int64_t row0,
                       const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st) {
   if (S <= 0) return;
   RopeTables rt = rope ? *rope : RopeTables{nullptr, nullptr, nullptr, 0, 0, 0};
-  k_norm_rope<T><<<(int)S, 256, 0, st>>>(src, ld, col, h, d, eps, g, dst, head_stride, row0, rt,
+  k_norm_rope<T><<<(int)S, 256, 0, st>>>(src, ld, col, h, d, eps, g, out_scale, dst, head_stride, row0, rt,
                                          rope ? 1 : 0, frame0, tok_h > 0 ? tok_h : 1, tok_w > 0 ? tok_w : 1);
 }
-template void launch_norm_rope<float>(const float*, int64_t, int, int64_t, int, int, float, const float*, float*, int64_t, int64_t, const RopeTables*, int, int, int, hipStream_t);
-template void launch_norm_rope<bf16_t>(const bf16_t*, int64_t, int, int64_t, int, int, float, const float*, bf16_t*, int64_t, int64_t, const RopeTables*, int, int, int, hipStream_t);
+template void launch_norm_rope<float>(const float*, int64_t, int, int64_t, int, int, float, const float*, float, float*, int64_t, int64_t, const RopeTables*, int, int, int, hipStream_t);
+template void launch_norm_rope<bf16_t>(const bf16_t*, int64_t, int, int64_t, int, int, float, const float*, float, bf16_t*, int64_t, int64_t, const RopeTables*, int, int, int, hipStream_t);
 
 // ---------------------------------------------------------------- V -> V^T (per head [d][L])
 // 64x64 tile through LDS: reads are contiguous along channels, writes along tokens.

@@ -4,7 +4,8 @@
 // Block tile BM x BN x 64, WGM x WGN wavefronts, each owning a (BM/WGM) x (BN/WGN) sub-tile built from
 // v_mfma_f32_32x32x16_bf16.  Global -> registers -> LDS staging with two LDS buffers: the loads of
 // k-tile i+1 are in flight while k-tile i is multiplied.  LDS rows are 128 bytes (64 bf16); the
-// 16-byte chunk index is XOR-swizzled with the row so that fragment reads spread over all banks.
+// 16-byte chunk index is XOR-swizzled with (row >> 1) & 7: LDS serves 16 lanes x 16 bytes per cycle from
+// 64 banks, i.e. two 128-byte rows per bank sweep, and the swizzle spreads a column of chunks over all of them.
 #include "kernels.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -37,13 +38,13 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   for (int i = 0; i < CA; ++i) {
     const int c = tid + i * NT, row = c >> 3, kc = c & 7;
     ga[i] = (const uint4*)(A + (m0 + row) * lda + kc * 8);
-    sa[i] = row * 8 + (kc ^ (row & 7));
+    sa[i] = row * 8 + (kc ^ ((row >> 1) & 7));
   }
 #pragma unroll
   for (int i = 0; i < CB; ++i) {
     const int c = tid + i * NT, row = c >> 3, kc = c & 7;
     gb[i] = (const uint4*)(Bt + (n0 + row) * ldb + kc * 8);
-    sb[i] = BM * 8 + row * 8 + (kc ^ (row & 7));
+    sb[i] = BM * 8 + row * 8 + (kc ^ ((row >> 1) & 7));
   }
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -81,12 +82,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int row = wm * WM + i * 32 + lr;
-        af[i] = __builtin_bit_cast(bf16x8, buf[row * 8 + (kc ^ (row & 7))]);
+        af[i] = __builtin_bit_cast(bf16x8, buf[row * 8 + (kc ^ ((row >> 1) & 7))]);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         const int row = wn * WN + j * 32 + lr;
-        bfr[j] = __builtin_bit_cast(bf16x8, buf[BM * 8 + row * 8 + (kc ^ (row & 7))]);
+        bfr[j] = __builtin_bit_cast(bf16x8, buf[BM * 8 + row * 8 + (kc ^ ((row >> 1) & 7))]);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)

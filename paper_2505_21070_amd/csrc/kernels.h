@@ -15,10 +15,10 @@ struct RopeTables {            // cos/sin pairs: tab[pos][pair] = (cos, sin)
   int c_f, c_h, c_w;           // pairs per axis
 };
 // One source matrix src[S, ld] holding an un-normalised projection in columns [col, col+D).
-// dst[head][row0 + s][d] = RoPE(RMSNorm_D(src[s]) * g) ; rope == nullptr skips the rotation.
+// dst[head][row0 + s][d] = out_scale * RoPE(RMSNorm_D(src[s]) * g) ; rope == nullptr skips the rotation.
 template <typename T>
 void launch_norm_rope(const T* src, int64_t ld, int col, int64_t S, int h, int d, float eps,
-                      const float* g, T* dst, int64_t head_stride, int64_t row0,
+                      const float* g, float out_scale, T* dst, int64_t head_stride, int64_t row0,
                       const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st);
 // vt[head][c][col0 + s] = src[s, col + head*d + c]
 template <typename T>
@@ -64,8 +64,10 @@ void launch_attn_f32(const float* q, int64_t q_head_stride, const float* k, int6
 void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M,
                       int64_t N, int64_t K, int epi, const EpiArgs& e, hipStream_t st);
 // ---- attn_bf16.hip : flash attention on MFMA, head_dim 64 or 128 ------------------------------
-// q readable for roundup(S, 256) rows per head; k rows / vt columns readable (finite in vt) up to
+// q must already be multiplied by log2(e)/sqrt(d) (attn_bf16_q_scale) and be readable for
+// roundup(S, 256) rows per head; k rows / vt columns readable (finite in vt) up to
 // k_row0 + roundup(L, 64).
+inline float attn_bf16_q_scale(int d) { return 1.4426950408889634f / sqrtf((float)d); }
 void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
                       int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
                       int h, int d, bf16_t* out, int64_t ldo, hipStream_t st);

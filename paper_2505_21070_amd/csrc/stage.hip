@@ -180,6 +180,7 @@ extern "C" size_t dp_stage_workspace_bytes(const dp_stage_config* cfg) {
 // ------------------------------------------------------------------------------------------ typed helpers
 template <typename T> struct Path;
 template <> struct Path<float> {
+  static float q_scale(int) { return 1.f; }             // the fp32 attention kernel scales by 1/sqrt(d) itself
   // y = x[M,K] * W[K,N] (+epilogue); `wt` unused
   static void gemm(const void* A, int64_t lda, const void* W, const void* /*wt*/, int64_t M, int64_t N,
                    int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
@@ -191,6 +192,7 @@ template <> struct Path<float> {
   }
 };
 template <> struct Path<bf16_t> {
+  static float q_scale(int d) { return attn_bf16_q_scale(d); }   // queries carry log2(e)/sqrt(d)
   static void gemm(const void* A, int64_t lda, const void* /*W*/, const void* wt, int64_t M, int64_t N,
                    int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
     launch_gemm_bf16((const bf16_t*)A, lda, (const bf16_t*)wt, K, M, N, K, epi, e, st);
@@ -253,7 +255,7 @@ static void init_typed(dp_stage* s, const void* text, hipStream_t st) {
     const dp_layer_weights& w = s->lw[(size_t)l]; LayerMem& m = s->lm[(size_t)l];
     if (bf) launch_transpose_pad<T>((const T*)w.cwk, D, D, (T*)s->wtmp, rup(D, 256), st);
     Path<T>::gemm(ctx, D, w.cwk, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbk), st);
-    launch_norm_rope<T>((const T*)s->raw, D, 0, Lt, h, d, c.eps, m.cgk, (T*)m.tk, s->Ltpad * d, 0, nullptr, 0, 1, 1, st);
+    launch_norm_rope<T>((const T*)s->raw, D, 0, Lt, h, d, c.eps, m.cgk, 1.f, (T*)m.tk, s->Ltpad * d, 0, nullptr, 0, 1, 1, st);
     if (bf) launch_transpose_pad<T>((const T*)w.cwv, D, D, (T*)s->wtmp, rup(D, 256), st);
     Path<T>::gemm(ctx, D, w.cwv, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbv), st);
     launch_v_transpose<T>((const T*)s->raw, D, 0, Lt, h, d, (T*)m.tvt, s->Ltpad, 0, st);
@@ -331,8 +333,8 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
            Path<T>::gemm(s->hbuf, D, w.wv, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + 2 * D, 3 * D, w.bv), st));
     }
     PROF(DP_PROF_NORM_ROPE,
-         launch_norm_rope<T>((const T*)s->raw, 3 * D, 0, S, h, d, c.eps, m.gq, (T*)s->qbuf, s->Spad * d, 0, &s->rt, frame0, c.tok_h, c.tok_w, st);
-         launch_norm_rope<T>((const T*)s->raw, 3 * D, (int)D, S, h, d, c.eps, m.gk, (T*)m.kbuf, kv_hs, s->Ncmax, &s->rt, frame0, c.tok_h, c.tok_w, st);
+         launch_norm_rope<T>((const T*)s->raw, 3 * D, 0, S, h, d, c.eps, m.gq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, &s->rt, frame0, c.tok_h, c.tok_w, st);
+         launch_norm_rope<T>((const T*)s->raw, 3 * D, (int)D, S, h, d, c.eps, m.gk, 1.f, (T*)m.kbuf, kv_hs, s->Ncmax, &s->rt, frame0, c.tok_h, c.tok_w, st);
          launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, s->Ncmax, st));
     PROF(DP_PROF_SELF_ATTN,
          Path<T>::attn(s->qbuf, s->Spad * d, m.kbuf, kv_hs, s->Ncmax - s->cache_len, m.vtbuf, s->Lpad, S,
@@ -344,7 +346,7 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
     PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, m.ln3g, m.ln3b, 0, st));
     PROF(DP_PROF_CROSS_Q_GEMM, Path<T>::gemm(s->hbuf, D, w.cwq, m.cwq_t, S, D, D, EPI_STORE, epi_store(s->raw, D, w.cbq), st));
     PROF(DP_PROF_NORM_ROPE,
-         launch_norm_rope<T>((const T*)s->raw, D, 0, S, h, d, c.eps, m.cgq, (T*)s->qbuf, s->Spad * d, 0, nullptr, 0, 1, 1, st));
+         launch_norm_rope<T>((const T*)s->raw, D, 0, S, h, d, c.eps, m.cgq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, nullptr, 0, 1, 1, st));
     PROF(DP_PROF_CROSS_ATTN,
          Path<T>::attn(s->qbuf, s->Spad * d, m.tk, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, st));
     PROF(DP_PROF_CROSS_O_GEMM, Path<T>::gemm(s->attn_o, D, w.cwo, m.cwo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.cbo, nullptr), st));

@@ -175,3 +175,32 @@ def test_error_paths_leave_gpu_alone():
     sw = B.StageWeights()
     rc = B._lib.dp_stage_init(B.C.byref(conf), B.C.byref(sw), x.data_ptr(), ws.data_ptr(), 1024, None, B.C.byref(h))
     assert rc == B.DP_EINVAL and not h.value      # null weights
+
+
+def test_peaked_attention_takes_the_safe_pass():
+    """Large cross-attention q/k gains make base-2 logits of later keys exceed those of the first 32 keys
+    by far more than 2^100, so the fixed-reference fast pass of the attention kernel overflows and the
+    kernel must recompute those blocks with the classical online softmax.  The kernel's output is
+    checked against a float64 softmax over the very q, K, V it read (peeked from the library), because
+    at such logit ranges the bf16 rounding of q and K, not the kernel, dominates any end-to-end error."""
+    cfg, w, text, blocks = synth.make_case("small_bf16", seed=8, strong_gate=True)
+    for lw in w["layers"]:
+        for k in ("cgq", "cgk"):
+            lw[k] = synth.round_to(lw[k] * 12.0, "bf16")
+    nf = cfg["block_frames"]
+    g = gpu_stage(cfg, w, text, max_abs_frames=16)
+    g.forward(to_dev(blocks[1], cfg), nf, 0, T_CUR)
+    li, h, d = cfg["n_layers"] - 1, cfg["n_heads"], cfg["head_dim"]
+    q = to_np(g.peek("q", li))            # already multiplied by log2(e)/sqrt(d)
+    kt, vt = to_np(g.peek("text_k", li)), to_np(g.peek("text_v", li))
+    got = to_np(g.peek("cross_attn", li))
+    ref = np.zeros_like(got)
+    spread = 0.0
+    for hd in range(h):
+        sl = slice(hd * d, (hd + 1) * d)
+        s2 = q[:, sl] @ kt[:, sl].T                              # base-2 logits
+        spread = max(spread, float((s2[:, 32:].max(1) - s2[:, :32].max(1)).max()))
+        p = np.exp2(s2 - s2.max(1, keepdims=True))
+        ref[:, sl] = (p / p.sum(1, keepdims=True)) @ vt[:, sl]
+    assert spread > 110.0, spread                                # beyond what the fast pass can hold
+    check("peaked/cross_attn", got, ref, "bf16")
