@@ -54,7 +54,8 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
                                                   const bf16_t* __restrict__ k, int64_t k_head_stride,
                                                   int64_t k_row0, const bf16_t* __restrict__ vt,
                                                   int64_t vt_row_stride, int64_t S, int64_t L,
-                                                  bf16_t* __restrict__ out, int64_t ldo) {
+                                                  bf16_t* __restrict__ out, int64_t ldo, int qblocks,
+                                                  int n_heads) {
   constexpr int CR = HD / 8;                 // 16-byte chunks per K row
   constexpr int KS = HD / 16;                // MFMA k-steps over the head dim
   constexpr int DT = HD / 32;                // 32-row tiles of O^T
@@ -68,8 +69,13 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qt = wave & 3, kg = wave >> 2;
   const int lr = lane & 31, lg = lane >> 5;
-  const int head = blockIdx.y;
-  const int64_t q0 = (int64_t)blockIdx.x * 128 + qt * 32;
+  // Blocks are dealt round-robin over the 8 XCDs, each with its own L2: give every XCD a contiguous run
+  // of (head, query block) work ids so that the blocks streaming one head's K/V share an L2.  The grid
+  // is padded to a multiple of 8; the padding blocks have nothing to do.
+  const int wid = (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3);
+  if (wid >= qblocks * n_heads) return;
+  const int head = wid / qblocks;
+  const int64_t q0 = (int64_t)(wid % qblocks) * 128 + qt * 32;
   uint4* const kbuf = smem + kg * GCH;
   uint4* const vbuf = kbuf + 2 * KCH;
 
@@ -275,7 +281,8 @@ void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, i
                       int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
                       int h, int d, bf16_t* out, int64_t ldo, hipStream_t st) {
   if (S <= 0 || L <= 0) return;
-  dim3 grid((unsigned)((S + 127) / 128), (unsigned)h);
+  const int qblocks = (int)((S + 127) / 128);
+  dim3 grid((unsigned)((qblocks * h + 7) / 8 * 8));
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)k_attn_bf16<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16);
@@ -283,7 +290,7 @@ void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, i
     attr_done = true;
   }
   if (d == 128)
-    k_attn_bf16<128><<<grid, 512, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo);
+    k_attn_bf16<128><<<grid, 512, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, h);
   else
-    k_attn_bf16<64><<<grid, 512, 2 * (2 * 64 * 8 + 2 * 64 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo);
+    k_attn_bf16<64><<<grid, 512, 2 * (2 * 64 * 8 + 2 * 64 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, h);
 }

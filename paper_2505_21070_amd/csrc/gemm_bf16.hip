@@ -41,10 +41,11 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
-  // tiles of one XCD (blocks are dealt round-robin over 8 XCDs) form a contiguous run of work ids
-  const int nblk = gridDim.x;
-  int pid = blockIdx.x;
-  if (nblk % 8 == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  // Blocks are dealt round-robin over the 8 XCDs, each with its own L2: give every XCD a contiguous run
+  // of work ids (row-major tiles, so neighbours share the A row-panel and walk the B panels together).
+  // The grid is padded to a multiple of 8; the padding blocks have nothing to do.
+  const int pid = (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3);
+  if (pid >= tiles * splits) return;
   const int split = pid / tiles, tile = pid % tiles;
   const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
   const int KT_all = (int)(K / 64);
@@ -158,7 +159,7 @@ static void launch_cfg(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t l
     (void)hipFuncSetAttribute((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  dim3 grid((unsigned)(tm * tn * splits));
+  dim3 grid((unsigned)((tm * tn * splits + 7) / 8 * 8));
   if (epi == EPI_STORE) k_gemm_bf16<BM, BN, WGM, WGN, EPI_STORE><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, splits, e);
   else if (epi == EPI_GELU) k_gemm_bf16<BM, BN, WGM, WGN, EPI_GELU><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, splits, e);
   else k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, splits, e);

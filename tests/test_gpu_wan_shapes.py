@@ -1,0 +1,72 @@
+"""GPU parity at the benchmark's full sizes (Wan-1.3B-shaped stage, the launch configuration bench.py
+times): 6240-token blocks, 3120 cached tokens, 512 text tokens, dim 1536, 12 heads x 128, FFN 8960, bf16.
+The whole-stage oracle would need minutes of CPU here, so every layer is checked teacher-forced: the GPU
+runs the stage as a chain of one-layer stages (Eq. 1 of the paper: the chunks compose), the oracle gets
+each layer's GPU input, and the layer outputs are compared on sampled query rows (each of which attends
+over ALL keys: cached + block), the keys/values on all rows of sampled heads."""
+import numpy as np
+import pytest
+import torch
+
+from harness import check, gpu_stage, to_dev, to_np
+from oracle.stage import OracleStage, token_positions
+from paper_2505_21070_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_wan1p3b_stage_layers_teacher_forced():
+    cfg, w, text, blocks = synth.make_case("wan1p3b_stage", seed=0, strong_gate=True)
+    nf, nc, tok = cfg["block_frames"], cfg["cache_frames"], cfg["tok_h"] * cfg["tok_w"]
+    S, Nc, D = nf * tok, nc * tok, cfg["dim"]
+    one = dict(cfg, n_layers=1)
+    wn = synth.to_numpy(w)
+    rng = np.random.default_rng(0)
+    rows = np.sort(np.concatenate([[0, 1, S - 1, 1559, 1560, 3119, 3120], rng.choice(S, size=121, replace=False)]))
+    x_nb, x_cur = to_dev(blocks[0], cfg), to_dev(blocks[1], cfg)
+    for li in range(cfg["n_layers"]):
+        lw = {"stage": w["stage"], "layers": [w["layers"][li]]}
+        g = gpu_stage(one, lw, text, max_abs_frames=16)
+        o = OracleStage(one, {"stage": wn["stage"], "layers": [wn["layers"][li]]}, text.numpy())
+        # neighbour block (later, noisier) first; its first cache_frames frames become the cache
+        y_nb = g.forward(x_nb, nf, nf, 625.0)
+        g.cache_update(0, nc)
+        # oracle cache from the same layer input: K/V rows of a frame depend only on that frame's tokens
+        xin_nb = to_np(x_nb)[:Nc]
+        e_nb = o.modulation(625.0)
+        _, k_c, v_c = o.layer(0, xin_nb, e_nb, token_positions(nc, nf, cfg["tok_h"], cfg["tok_w"]), None, rows=np.array([0]))
+        check(f"L{li}/cache_k", to_np(g.peek("cache_k", 0)), k_c, "bf16")
+        check(f"L{li}/cache_v", to_np(g.peek("cache_v", 0)), v_c, "bf16")
+        # current block
+        y = g.forward(x_cur, nf, 0, 500.0)
+        xin = to_np(x_cur)
+        ref, k, v = o.layer(0, xin, o.modulation(500.0), token_positions(nf, 0, cfg["tok_h"], cfg["tok_w"]), (k_c, v_c), rows=rows)
+        check(f"L{li}/k", to_np(g.peek("k", 0)), k, "bf16")
+        check(f"L{li}/v", to_np(g.peek("v", 0)), v, "bf16")
+        xres = to_np(g.peek("x_res", 0))[rows]
+        check(f"L{li}/x_res", xres, ref, "bf16")
+        check(f"L{li}/delta", xres - xin[rows], ref - xin[rows], "bf16")
+        check(f"L{li}/x_out", to_np(y)[rows], ref, "bf16")
+        assert torch.isfinite(y.float()).all()
+        x_nb, x_cur = y_nb, y            # next layer's inputs are this layer's GPU outputs
+        del g
+        torch.cuda.empty_cache()
+
+
+def test_wan1p3b_whole_stage_equals_layer_chain():
+    """The 4-layer stage that bench.py times against the chain of one-layer stages checked above."""
+    cfg, w, text, blocks = synth.make_case("wan1p3b_stage", seed=0, strong_gate=True)
+    nf, nc = cfg["block_frames"], cfg["cache_frames"]
+    whole = gpu_stage(cfg, w, text, max_abs_frames=16)
+    chain = [gpu_stage(dict(cfg, n_layers=1), {"stage": w["stage"], "layers": [w["layers"][i]]}, text, max_abs_frames=16)
+             for i in range(cfg["n_layers"])]
+    def run(stages, x, f0, t):
+        for s in stages:
+            x = s.forward(x, nf, f0, t)
+        return x
+    run([whole], to_dev(blocks[0], cfg), nf, 625.0); whole.cache_update(0, nc)
+    run(chain, to_dev(blocks[0], cfg), nf, 625.0); [s.cache_update(0, nc) for s in chain]
+    a = run([whole], to_dev(blocks[1], cfg), 0, 500.0)
+    b = run(chain, to_dev(blocks[1], cfg), 0, 500.0)
+    check("whole_vs_chain", to_np(b), to_np(a), "bf16")     # differs only by bf16 rounding at the hand-overs
+    assert float(np.linalg.norm(to_np(a) - to_np(b)) / np.linalg.norm(to_np(a))) < 5e-3
