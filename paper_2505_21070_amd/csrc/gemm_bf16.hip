@@ -47,7 +47,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   const int pid = (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3);
   if (pid >= tiles * splits) return;
   const int split = pid / tiles, tile = pid % tiles;
-  const int64_t m0 = (int64_t)(tile / tiles_n) * BM, n0 = (int64_t)(tile % tiles_n) * BN;
+  // tiles are walked in bands of 4 tile rows, column by column inside a band: the ~32 blocks an XCD runs
+  // at a time then cover about 4 x 8 tiles and share 4 A panels and 8 B panels instead of 1 and 32
+  const int tiles_m = tiles / tiles_n;
+  const int band = tile / (4 * tiles_n), in_band = tile % (4 * tiles_n);
+  const int band_rows = tiles_m - band * 4 < 4 ? tiles_m - band * 4 : 4;
+  const int64_t m0 = (int64_t)(band * 4 + in_band % band_rows) * BM, n0 = (int64_t)(in_band / band_rows) * BN;
   const int KT_all = (int)(K / 64);
   const int kt0 = (int)((int64_t)KT_all * split / splits), KT = (int)((int64_t)KT_all * (split + 1) / splits) - kt0;
 
