@@ -22,6 +22,11 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_FP32_TFLOPS = 157.3      # fp32 vector
 PEAK_HBM_GBS = 8000.0         # HBM3E, published
 
+# HBM-side bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this command
+# (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for the plain cache-copy kernel of
+# known size; figures and commands in profiles/bench_wan1p3b_stage.md.  None where not measured.
+MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 206.8e6}
+
 
 def class_work(cfg, S, Nc):
     """Algorithmic work per launch of each kernel class: (flops, bytes).  bytes only for the HBM-bound ones."""
@@ -164,7 +169,8 @@ def main():
         peak = PEAK_BF16_TFLOPS if cfg["dtype"] == "bf16" else PEAK_FP32_TFLOPS
         achieved = fl / (dom_ms / dom_n * 1e-3) / 1e12
         roof = {"kernel": dominant, "bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "achieved": achieved,
-                "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dominant)),
                 "avg_launch_ms": dom_ms / dom_n, "launches": dom_n}
     else:
         achieved = by / (dom_ms / dom_n * 1e-3) / 1e9
