@@ -109,81 +109,111 @@ template void launch_ln_modulate<float>(const float*, float*, int64_t, int, floa
 template void launch_ln_modulate<bf16_t>(const float*, bf16_t*, int64_t, int, float, const float*, const float*, int, hipStream_t);
 
 // ---------------------------------------------------------------- RMSNorm over D + 3D RoPE, head-major output
-// One block per token.  Each thread owns channel pairs (2p, 2p+1), p = tid, tid + 256, ...
+// One block per token and job (blockIdx.y: e.g. q and k of the same row).  A thread owns groups of 8
+// consecutive channels (one 16-byte access for bf16), kept in registers between the sum-of-squares
+// pass and the normalise/rotate/store pass, so the row is read once.
+template <typename T> struct alignas(sizeof(T) * 8) Vec8 { T v[8]; };
+
 template <typename T>
-__global__ __launch_bounds__(256) void k_norm_rope(const T* __restrict__ src, int64_t ld, int col, int h,
-                                                   int d, float eps, const float* __restrict__ g, float out_scale,
-                                                   T* __restrict__ dst, int64_t head_stride, int64_t row0,
-                                                   RopeTables rt, int use_rope, int frame0, int tok_h,
-                                                   int tok_w) {
+__global__ __launch_bounds__(256) void k_norm_rope(const T* __restrict__ src, int64_t ld, int h, int d, float eps,
+                                                   NormRopeJob<T> j0, NormRopeJob<T> j1, int64_t row0,
+                                                   RopeTables rt, int frame0, int tok_h, int tok_w) {
   __shared__ float red[4];
+  const NormRopeJob<T> job = blockIdx.y == 0 ? j0 : j1;
   const int64_t s = blockIdx.x;
-  const int D = h * d, npair = D >> 1;
-  const T* row = src + s * ld + col;
+  const int D = h * d, nvec = D >> 3;
+  const Vec8<T>* row = (const Vec8<T>*)(src + s * ld + job.col);
+  float v[4][8];
   float sq = 0.f;
-  for (int p = threadIdx.x; p < npair; p += 256) {
-    const float a = Elem<T>::ld(row + 2 * p), b = Elem<T>::ld(row + 2 * p + 1);
-    sq += a * a + b * b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int vi = threadIdx.x + i * 256;
+    if (vi < nvec) {
+      const Vec8<T> t = row[vi];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { v[i][e] = Elem<T>::ld(&t.v[e]); sq += v[i][e] * v[i][e]; }
+    }
   }
   sq = wave_sum(sq);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
   __syncthreads();
-  const float r = rsqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)D + eps) * out_scale;
+  const float r = rsqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)D + eps) * job.out_scale;
   const int tok = tok_h * tok_w;
   const int f = frame0 + (int)(s / tok), rem = (int)(s % tok);
   const int y = rem / tok_w, x = rem % tok_w;
-  const int half = d >> 1;
-  for (int p = threadIdx.x; p < npair; p += 256) {
-    const int head = p / half, i = p % half;
-    float a = Elem<T>::ld(row + 2 * p) * r * g[2 * p];
-    float b = Elem<T>::ld(row + 2 * p + 1) * r * g[2 * p + 1];
-    if (use_rope) {
-      float2 cs;
-      if (i < rt.c_f) cs = rt.f[(int64_t)f * rt.c_f + i];
-      else if (i < rt.c_f + rt.c_h) cs = rt.y[y * rt.c_h + (i - rt.c_f)];
-      else cs = rt.x[x * rt.c_w + (i - rt.c_f - rt.c_h)];
-      const float a2 = a * cs.x - b * cs.y, b2 = a * cs.y + b * cs.x;
-      a = a2; b = b2;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int vi = threadIdx.x + i * 256;
+    if (vi < nvec) {
+      const int c0 = vi * 8, head = c0 / d, p0 = (c0 % d) >> 1;        // first channel, its head, first pair in the head
+      const float4 g0 = *(const float4*)(job.g + c0), g1 = *(const float4*)(job.g + c0 + 4);
+      const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      Vec8<T> o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float a = v[i][2 * e] * r * gg[2 * e], b = v[i][2 * e + 1] * r * gg[2 * e + 1];
+        if (job.rope) {
+          const int pi = p0 + e;
+          float2 cs;
+          if (pi < rt.c_f) cs = rt.f[(int64_t)f * rt.c_f + pi];
+          else if (pi < rt.c_f + rt.c_h) cs = rt.y[y * rt.c_h + (pi - rt.c_f)];
+          else cs = rt.x[x * rt.c_w + (pi - rt.c_f - rt.c_h)];
+          const float a2 = a * cs.x - b * cs.y, b2 = a * cs.y + b * cs.x;
+          a = a2; b = b2;
+        }
+        Elem<T>::st(&o.v[2 * e], a);
+        Elem<T>::st(&o.v[2 * e + 1], b);
+      }
+      *(Vec8<T>*)(job.dst + (int64_t)head * job.head_stride + (job.row0 + s) * d + (c0 % d)) = o;
     }
-    T* o = dst + (int64_t)head * head_stride + (row0 + s) * d + 2 * i;
-    Elem<T>::st(o, a);
-    Elem<T>::st(o + 1, b);
   }
 }
 template <typename T>
-void launch_norm_rope(const T* src, int64_t ld, int col, int64_t S, int h, int d, float eps,
-                      const float* g, float out_scale, T* dst, int64_t head_stride, int64_t row0,
-                      const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st) {
-  if (S <= 0) return;
+void launch_norm_rope(const T* src, int64_t ld, int64_t S, int h, int d, float eps, const NormRopeJob<T>* jobs,
+                      int n_jobs, const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st) {
+  if (S <= 0 || n_jobs <= 0) return;
   RopeTables rt = rope ? *rope : RopeTables{nullptr, nullptr, nullptr, 0, 0, 0};
-  k_norm_rope<T><<<(int)S, 256, 0, st>>>(src, ld, col, h, d, eps, g, out_scale, dst, head_stride, row0, rt,
-                                         rope ? 1 : 0, frame0, tok_h > 0 ? tok_h : 1, tok_w > 0 ? tok_w : 1);
+  NormRopeJob<T> j0 = jobs[0], j1 = jobs[n_jobs > 1 ? 1 : 0];
+  if (!rope) { j0.rope = 0; j1.rope = 0; }
+  k_norm_rope<T><<<dim3((unsigned)S, (unsigned)(n_jobs > 1 ? 2 : 1)), 256, 0, st>>>(
+      src, ld, h, d, eps, j0, j1, 0, rt, frame0, tok_h > 0 ? tok_h : 1, tok_w > 0 ? tok_w : 1);
 }
-template void launch_norm_rope<float>(const float*, int64_t, int, int64_t, int, int, float, const float*, float, float*, int64_t, int64_t, const RopeTables*, int, int, int, hipStream_t);
-template void launch_norm_rope<bf16_t>(const bf16_t*, int64_t, int, int64_t, int, int, float, const float*, float, bf16_t*, int64_t, int64_t, const RopeTables*, int, int, int, hipStream_t);
+template void launch_norm_rope<float>(const float*, int64_t, int64_t, int, int, float, const NormRopeJob<float>*, int, const RopeTables*, int, int, int, hipStream_t);
+template void launch_norm_rope<bf16_t>(const bf16_t*, int64_t, int64_t, int, int, float, const NormRopeJob<bf16_t>*, int, const RopeTables*, int, int, int, hipStream_t);
 
 // ---------------------------------------------------------------- V -> V^T (per head [d][L])
-// 64x64 tile through LDS: reads are contiguous along channels, writes along tokens.
+// 64 tokens x 64 channels through LDS: 16-byte reads along channels, 16-byte writes along tokens.
 template <typename T>
 __global__ __launch_bounds__(256) void k_v_transpose(const T* __restrict__ src, int64_t ld, int col, int64_t S,
                                                      int D, int d, T* __restrict__ vt, int64_t row_stride,
-                                                     int64_t col0) {
-  __shared__ T tile[64][65];
+                                                     int64_t col0, int vec_ok) {
+  __shared__ __align__(32) T tile[64][72];       // [channel][token], row padded, rows stay vector-aligned
   const int64_t s0 = (int64_t)blockIdx.x * 64;
   const int c0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int r = ty; r < 64; r += 4) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int r = (t >> 3) + pass * 32, cc = (t & 7) * 8;
     const int64_t s = s0 + r;
-    const int c = c0 + tx;
-    tile[r][tx] = (s < S && c < D) ? src[s * ld + col + c] : (T)0;
+    Vec8<T> x;
+    if (s < S && c0 + cc < D) x = *(const Vec8<T>*)(src + s * ld + col + c0 + cc);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x.v[e] = (T)0;
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) tile[cc + e][r] = x.v[e];
   }
   __syncthreads();
-  for (int r = ty; r < 64; r += 4) {
-    const int c = c0 + r;           // channel
-    const int64_t s = s0 + tx;      // token
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int ch = (t >> 3) + pass * 32, tk = (t & 7) * 8;
+    const int c = c0 + ch;
+    const int64_t s = s0 + tk;
     if (c < D && s < S) {
-      const int head = c / d, cc = c % d;
-      vt[((int64_t)head * d + cc) * row_stride + col0 + s] = tile[tx][r];
+      T* o = vt + (int64_t)c * row_stride + col0 + s;     // channel c = head*d + cc: row c of [h*d][row_stride]
+      if (vec_ok && s + 8 <= S) *(Vec8<T>*)o = *(const Vec8<T>*)&tile[ch][tk];
+      else for (int e = 0; e < 8 && s + e < S; ++e) o[e] = tile[ch][tk + e];
     }
   }
 }
@@ -192,7 +222,8 @@ void launch_v_transpose(const T* src, int64_t ld, int col, int64_t S, int h, int
                         int64_t row_stride, int64_t col0, hipStream_t st) {
   if (S <= 0) return;
   dim3 grid(cdiv(S, 64), cdiv(h * d, 64));
-  k_v_transpose<T><<<grid, 256, 0, st>>>(src, ld, col, S, h * d, d, vt, row_stride, col0);
+  const int vec_ok = (col0 % 8 == 0) && (row_stride % 8 == 0) && ((uintptr_t)vt % (8 * sizeof(T)) == 0);
+  k_v_transpose<T><<<grid, 256, 0, st>>>(src, ld, col, S, h * d, d, vt, row_stride, col0, vec_ok);
 }
 template void launch_v_transpose<float>(const float*, int64_t, int, int64_t, int, int, float*, int64_t, int64_t, hipStream_t);
 template void launch_v_transpose<bf16_t>(const bf16_t*, int64_t, int, int64_t, int, int, bf16_t*, int64_t, int64_t, hipStream_t);
@@ -272,30 +303,41 @@ void launch_sinusoid(float t, int freq_dim, float* out, hipStream_t st) {
   k_sinusoid<<<cdiv(freq_dim / 2, 64), 64, 0, st>>>(t, freq_dim, out);
 }
 
-// y[n] = sum_k act(x[k]) W[k,n] + b[n].  One thread per output column, 4 independent partial sums.
+// y[n] = sum_k act(x[k]) W[k,n] + b[n].  A block owns 64 output columns; its 16 wavefronts each take every
+// 16th row of W (coalesced 64-column reads) and the partial sums meet in LDS.
 template <typename T>
-__global__ __launch_bounds__(256) void k_gemv(const float* __restrict__ x, int K, const T* __restrict__ W,
-                                              const T* __restrict__ b, int N, int silu_in,
-                                              float* __restrict__ y) {
-  extern __shared__ float xs[];
-  for (int k = threadIdx.x; k < K; k += 256) { const float v = x[k]; xs[k] = silu_in ? v / (1.0f + expf(-v)) : v; }
+__global__ __launch_bounds__(1024) void k_gemv(const float* __restrict__ x, int K, const T* __restrict__ W,
+                                               const T* __restrict__ b, int N, int silu_in,
+                                               float* __restrict__ y) {
+  extern __shared__ float xs[];            // K activations, then 16 x 64 partial sums
+  float* red = xs + K;
+  for (int k = threadIdx.x; k < K; k += 1024) { const float v = x[k]; xs[k] = silu_in ? v / (1.0f + expf(-v)) : v; }
   __syncthreads();
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= N) return;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + tx;
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-  int k = 0;
-  for (; k + 4 <= K; k += 4) {
-    a0 += xs[k] * Elem<T>::ld(W + (int64_t)k * N + n);
-    a1 += xs[k + 1] * Elem<T>::ld(W + (int64_t)(k + 1) * N + n);
-    a2 += xs[k + 2] * Elem<T>::ld(W + (int64_t)(k + 2) * N + n);
-    a3 += xs[k + 3] * Elem<T>::ld(W + (int64_t)(k + 3) * N + n);
+  if (n < N) {
+    int k = ty;
+    for (; k + 48 < K; k += 64) {
+      a0 += xs[k] * Elem<T>::ld(W + (int64_t)k * N + n);
+      a1 += xs[k + 16] * Elem<T>::ld(W + (int64_t)(k + 16) * N + n);
+      a2 += xs[k + 32] * Elem<T>::ld(W + (int64_t)(k + 32) * N + n);
+      a3 += xs[k + 48] * Elem<T>::ld(W + (int64_t)(k + 48) * N + n);
+    }
+    for (; k < K; k += 16) a0 += xs[k] * Elem<T>::ld(W + (int64_t)k * N + n);
   }
-  for (; k < K; ++k) a0 += xs[k] * Elem<T>::ld(W + (int64_t)k * N + n);
-  y[n] = ((a0 + a1) + (a2 + a3)) + (b ? Elem<T>::ld(b + n) : 0.f);
+  red[ty * 64 + tx] = (a0 + a1) + (a2 + a3);
+  __syncthreads();
+  if (ty == 0 && n < N) {
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += red[i * 64 + tx];
+    y[n] = sum + (b ? Elem<T>::ld(b + n) : 0.f);
+  }
 }
 template <typename T>
 void launch_gemv(const float* x, int K, const T* W, const T* b, int N, int silu_in, float* y, hipStream_t st) {
-  k_gemv<T><<<cdiv(N, 256), 256, (size_t)K * sizeof(float), st>>>(x, K, W, b, N, silu_in, y);
+  k_gemv<T><<<cdiv(N, 64), 1024, (size_t)(K + 1024) * sizeof(float), st>>>(x, K, W, b, N, silu_in, y);
 }
 template void launch_gemv<float>(const float*, int, const float*, const float*, int, int, float*, hipStream_t);
 template void launch_gemv<bf16_t>(const float*, int, const bf16_t*, const bf16_t*, int, int, float*, hipStream_t);

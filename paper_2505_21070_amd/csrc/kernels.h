@@ -14,12 +14,15 @@ struct RopeTables {            // cos/sin pairs: tab[pos][pair] = (cos, sin)
   const float2* f; const float2* y; const float2* x;
   int c_f, c_h, c_w;           // pairs per axis
 };
-// One source matrix src[S, ld] holding an un-normalised projection in columns [col, col+D).
-// dst[head][row0 + s][d] = out_scale * RoPE(RMSNorm_D(src[s]) * g) ; rope == nullptr skips the rotation.
+// src[S, ld] holds un-normalised projections; job j takes columns [col, col+D) of every row:
+// dst[head][row0 + s][d] = out_scale * RoPE(RMSNorm_D(src[s, col:col+D]) * g) ; rope == 0 skips the rotation.
+// Up to two jobs (e.g. q and k of the fused QKV output) run in one launch.  D % 8 == 0.
+template <typename T> struct NormRopeJob {
+  int col; const float* g; float out_scale; T* dst; int64_t head_stride; int64_t row0; int rope;
+};
 template <typename T>
-void launch_norm_rope(const T* src, int64_t ld, int col, int64_t S, int h, int d, float eps,
-                      const float* g, float out_scale, T* dst, int64_t head_stride, int64_t row0,
-                      const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st);
+void launch_norm_rope(const T* src, int64_t ld, int64_t S, int h, int d, float eps, const NormRopeJob<T>* jobs,
+                      int n_jobs, const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st);
 // vt[head][c][col0 + s] = src[s, col + head*d + c]
 template <typename T>
 void launch_v_transpose(const T* src, int64_t ld, int col, int64_t S, int h, int d, T* vt,

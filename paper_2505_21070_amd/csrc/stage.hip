@@ -255,7 +255,8 @@ static void init_typed(dp_stage* s, const void* text, hipStream_t st) {
     const dp_layer_weights& w = s->lw[(size_t)l]; LayerMem& m = s->lm[(size_t)l];
     if (bf) launch_transpose_pad<T>((const T*)w.cwk, D, D, (T*)s->wtmp, rup(D, 256), st);
     Path<T>::gemm(ctx, D, w.cwk, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbk), st);
-    launch_norm_rope<T>((const T*)s->raw, D, 0, Lt, h, d, c.eps, m.cgk, 1.f, (T*)m.tk, s->Ltpad * d, 0, nullptr, 0, 1, 1, st);
+    { const NormRopeJob<T> jk{0, m.cgk, 1.f, (T*)m.tk, s->Ltpad * d, 0, 0};
+      launch_norm_rope<T>((const T*)s->raw, D, Lt, h, d, c.eps, &jk, 1, nullptr, 0, 1, 1, st); }
     if (bf) launch_transpose_pad<T>((const T*)w.cwv, D, D, (T*)s->wtmp, rup(D, 256), st);
     Path<T>::gemm(ctx, D, w.cwv, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbv), st);
     launch_v_transpose<T>((const T*)s->raw, D, 0, Lt, h, d, (T*)m.tvt, s->Ltpad, 0, st);
@@ -333,8 +334,9 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
            Path<T>::gemm(s->hbuf, D, w.wv, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + 2 * D, 3 * D, w.bv), st));
     }
     PROF(DP_PROF_NORM_ROPE,
-         launch_norm_rope<T>((const T*)s->raw, 3 * D, 0, S, h, d, c.eps, m.gq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, &s->rt, frame0, c.tok_h, c.tok_w, st);
-         launch_norm_rope<T>((const T*)s->raw, 3 * D, (int)D, S, h, d, c.eps, m.gk, 1.f, (T*)m.kbuf, kv_hs, s->Ncmax, &s->rt, frame0, c.tok_h, c.tok_w, st);
+         const NormRopeJob<T> qk[2] = {{0, m.gq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, 1},
+                                       {(int)D, m.gk, 1.f, (T*)m.kbuf, kv_hs, s->Ncmax, 1}};
+         launch_norm_rope<T>((const T*)s->raw, 3 * D, S, h, d, c.eps, qk, 2, &s->rt, frame0, c.tok_h, c.tok_w, st);
          launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, s->Ncmax, st));
     PROF(DP_PROF_SELF_ATTN,
          Path<T>::attn(s->qbuf, s->Spad * d, m.kbuf, kv_hs, s->Ncmax - s->cache_len, m.vtbuf, s->Lpad, S,
@@ -346,7 +348,8 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
     PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, m.ln3g, m.ln3b, 0, st));
     PROF(DP_PROF_CROSS_Q_GEMM, Path<T>::gemm(s->hbuf, D, w.cwq, m.cwq_t, S, D, D, EPI_STORE, epi_store(s->raw, D, w.cbq), st));
     PROF(DP_PROF_NORM_ROPE,
-         launch_norm_rope<T>((const T*)s->raw, D, 0, S, h, d, c.eps, m.cgq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, nullptr, 0, 1, 1, st));
+         const NormRopeJob<T> cq{0, m.cgq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, 0};
+         launch_norm_rope<T>((const T*)s->raw, D, S, h, d, c.eps, &cq, 1, nullptr, 0, 1, 1, st));
     PROF(DP_PROF_CROSS_ATTN,
          Path<T>::attn(s->qbuf, s->Spad * d, m.tk, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, st));
     PROF(DP_PROF_CROSS_O_GEMM, Path<T>::gemm(s->attn_o, D, w.cwo, m.cwo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.cbo, nullptr), st));
