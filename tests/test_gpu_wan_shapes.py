@@ -70,3 +70,73 @@ def test_wan1p3b_whole_stage_equals_layer_chain():
     b = run(chain, to_dev(blocks[1], cfg), 0, 500.0)
     check("whole_vs_chain", to_np(b), to_np(a), "bf16")     # differs only by bf16 rounding at the hand-overs
     assert float(np.linalg.norm(to_np(a) - to_np(b)) / np.linalg.norm(to_np(a))) < 5e-3
+
+
+def test_wan14b_shaped_layer_teacher_forced():
+    """Wan-14B-shaped layer (dim 5120, 40 heads x 128, FFN 13824, 45x80 tokens per frame, 512 text tokens of
+    width 4096).  To keep the CPU oracle within a minute the block is 2 frames (7200 tokens) with 1 cached
+    frame (3600 tokens) instead of 4 + 2; tile shapes, head count and ragged tails are those of the full
+    configuration.  One layer, sampled query rows over all keys."""
+    cfg, w, text, blocks = synth.make_case("wan14b_stage", seed=1, strong_gate=True, n_layers=1,
+                                           block_frames=2, cache_frames=1)
+    nf, nc, tok = 2, 1, cfg["tok_h"] * cfg["tok_w"]
+    S, Nc = nf * tok, nc * tok
+    g = gpu_stage(cfg, w, text, max_abs_frames=8)
+    o = OracleStage(cfg, synth.to_numpy(w), text.numpy())
+    x_nb, x_cur = to_dev(blocks[0], cfg), to_dev(blocks[1], cfg)
+    g.forward(x_nb, nf, nf, 625.0)
+    g.cache_update(0, nc)
+    _, k_c, v_c = o.layer(0, to_np(x_nb)[:Nc], o.modulation(625.0), token_positions(nc, nf, cfg["tok_h"], cfg["tok_w"]),
+                          None, rows=np.array([0]))
+    check("14b/cache_k", to_np(g.peek("cache_k", 0)), k_c, "bf16")
+    y = g.forward(x_cur, nf, 0, 500.0)
+    rows = np.sort(np.concatenate([[0, S - 1, 3599, 3600], np.random.default_rng(3).choice(S, size=44, replace=False)]))
+    xin = to_np(x_cur)
+    ref, k, v = o.layer(0, xin, o.modulation(500.0), token_positions(nf, 0, cfg["tok_h"], cfg["tok_w"]), (k_c, v_c), rows=rows)
+    check("14b/k", to_np(g.peek("k", 0)), k, "bf16")
+    check("14b/v", to_np(g.peek("v", 0)), v, "bf16")
+    xres = to_np(g.peek("x_res", 0))[rows]
+    check("14b/x_res", xres, ref, "bf16")
+    check("14b/delta", xres - xin[rows], ref - xin[rows], "bf16")
+    assert torch.isfinite(y.float()).all()
+
+
+def test_wan1p3b_full_queue_sweep_properties():
+    """All 30 Wan-1.3B-shaped layers on one GPU running a block queue at full size (4-frame blocks of 6240
+    tokens, 2 cached frames): the library's schedule drives forward + cache hand-over; checked properties:
+    the tail block of a step (no cache source) equals the same block on a fresh stage with an empty cache
+    bit for bit, a block that reads a cache differs from its cache-free result, everything is finite, and a
+    sampled row block of the first layer's cache equals the oracle (teacher-forced, layer 1 is exact)."""
+    from paper_2505_21070_amd import binding as B
+    cfg, w, text, _ = synth.make_case("wan1p3b_full", seed=2, strong_gate=False, n_blocks=0)
+    nb, T, num_b, num_c = 3, 2, cfg["block_frames"], 2 * cfg["cache_frames"]
+    gen = torch.Generator().manual_seed(5)
+    xs = [to_dev(b, cfg) for b in synth.noise_pool_blocks(cfg, nb, num_b + num_c // 2, gen)]
+    g = gpu_stage(cfg, w, text, max_abs_frames=nb * num_b)
+    fresh = gpu_stage(cfg, w, text, max_abs_frames=nb * num_b)
+    sched = B.blockwise_schedule(T, nb, num_b, num_c, 0, 1000.0, "reverse")
+    assert len(sched) == T * nb
+    for e in sched:
+        x = xs[e["block"] - 1]
+        if e["cache_block"] == 0:
+            g.cache_update(0, 0)
+        y = g.forward(x, e["n_frames"], e["frame0"], e["timestep"])
+        assert torch.isfinite(y.float()).all()
+        ref_nocache = fresh.forward(x, e["n_frames"], e["frame0"], e["timestep"])
+        if e["cache_block"] == 0:
+            assert torch.equal(y, ref_nocache)
+        else:
+            assert not torch.equal(y, ref_nocache)
+        g.cache_update(0, num_c // 2)
+    # layer-1 cache of the last pass against the oracle (K/V rows depend only on their own tokens in layer 1)
+    e = sched[-1]
+    one = dict(cfg, n_layers=1)
+    wn = synth.to_numpy({"stage": w["stage"], "layers": w["layers"][:1]})
+    o = OracleStage(one, wn, text.numpy())
+    tok = cfg["tok_h"] * cfg["tok_w"]
+    rows = slice(0, 256)
+    xin = to_np(xs[e["block"] - 1])[:tok]
+    _, k1, v1 = o.layer(0, xin, o.modulation(e["timestep"]), token_positions(1, e["frame0"], cfg["tok_h"], cfg["tok_w"]),
+                        None, rows=np.array([0]))
+    check("queue/cache_k_layer1", to_np(g.peek("cache_k", 0))[:tok][rows], k1[rows], "bf16")
+    check("queue/cache_v_layer1", to_np(g.peek("cache_v", 0))[:tok][rows], v1[rows], "bf16")
