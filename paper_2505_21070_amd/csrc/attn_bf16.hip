@@ -55,7 +55,8 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
                                                   int64_t k_row0, const bf16_t* __restrict__ vt,
                                                   int64_t vt_row_stride, int64_t S, int64_t L,
                                                   bf16_t* __restrict__ out, int64_t ldo, int qblocks,
-                                                  int n_heads) {
+                                                  int n_full, int n_tail, int parts,
+                                                  float* __restrict__ partial) {
   constexpr int CR = HD / 8;                 // 16-byte chunks per K row
   constexpr int KS = HD / 16;                // MFMA k-steps over the head dim
   constexpr int DT = HD / 32;                // 32-row tiles of O^T
@@ -70,19 +71,34 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
   const int qt = wave & 3, kg = wave >> 2;
   const int lr = lane & 31, lg = lane >> 5;
   // Blocks are dealt round-robin over the 8 XCDs, each with its own L2: give every XCD a contiguous run
-  // of (head, query block) work ids so that the blocks streaming one head's K/V share an L2.  The grid
-  // is padded to a multiple of 8; the padding blocks have nothing to do.
-  const int wid = (int)(blockIdx.x & 7) * (int)(gridDim.x >> 3) + (int)(blockIdx.x >> 3);
-  if (wid >= qblocks * n_heads) return;
+  // of (head, query block) work ids so that the blocks streaming one head's K/V share an L2.  The first
+  // n_full blocks (a multiple of 8) each own a whole work id; the n_tail work ids after them are cut into
+  // `parts` key ranges each, one block per range, again padded to a multiple of 8 blocks that have nothing
+  // to do.
+  const int NKT = (int)((L + 63) / 64);
+  int wid, t0 = 0, t1 = NKT, slot = -1;
+  if ((int)blockIdx.x < n_full) {
+    wid = (int)(blockIdx.x & 7) * (n_full >> 3) + (int)(blockIdx.x >> 3);
+  } else {
+    const int local = (int)blockIdx.x - n_full, tail_grid = (int)gridDim.x - n_full;
+    const int pid = (local & 7) * (tail_grid >> 3) + (local >> 3);
+    if (pid >= n_tail * parts) return;
+    wid = n_full + pid / parts;
+    if (parts > 1) {
+      const int part = pid % parts;
+      t0 = (int)((int64_t)part * NKT / parts);
+      t1 = (int)((int64_t)(part + 1) * NKT / parts);
+      slot = pid;
+    }
+  }
   const int head = wid / qblocks;
   const int64_t q0 = (int64_t)(wid % qblocks) * 128 + qt * 32;
   uint4* const kbuf = smem + kg * GCH;
   uint4* const vbuf = kbuf + 2 * KCH;
 
   // this wavefront's share of the key tiles
-  const int NKT = (int)((L + 63) / 64);
-  const int n0 = (NKT + 1) / 2;                       // tiles of group 0; also the trip count for everyone
-  const int first = kg ? n0 : 0, cnt = kg ? NKT - n0 : n0;
+  const int n0 = (t1 - t0 + 1) / 2;                   // tiles of group 0; also the trip count for everyone
+  const int first = t0 + (kg ? n0 : 0), cnt = kg ? t1 - t0 - n0 : n0;
 
   // Q fragments stay in registers: B operand, column = query, 8 head-dim values per lane
   bf16x8 qf[KS];
@@ -255,10 +271,28 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
     const float m0 = empty ? -INFINITY : mrun;
     const float m = fmaxf(m0, m1);
     const float a0 = __builtin_amdgcn_exp2f(m0 - m), a1 = __builtin_amdgcn_exp2f(m1 - m);   // 2^-inf = 0
-    const float inv = 1.f / (ltot * a0 + l1 * a1);
-    const float w0 = a0 * inv, w1 = a1 * inv;
+    const float lall = ltot * a0 + l1 * a1;
     const int64_t qi = q0 + lr;
-    if (qi < S) {
+    if (slot >= 0) {
+      // one key range of a split work id: publish m, l and the unnormalised O^T for the merge kernel.
+      // Slot layout (floats): m[128], l[128], then O as [HD/4][128 queries][4 channels].
+      float* ps = partial + (size_t)slot * (256 + 128 * HD);
+      const int ql = qt * 32 + lr;
+      if (lg == 0) { ps[ql] = m; ps[128 + ql] = lall; }
+#pragma unroll
+      for (int a = 0; a < DT; ++a)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          float4 v;
+          v.x = oacc[a][g4 * 4 + 0] * a0 + mine[(2 + a * 16 + g4 * 4 + 0) * 64] * a1;
+          v.y = oacc[a][g4 * 4 + 1] * a0 + mine[(2 + a * 16 + g4 * 4 + 1) * 64] * a1;
+          v.z = oacc[a][g4 * 4 + 2] * a0 + mine[(2 + a * 16 + g4 * 4 + 2) * 64] * a1;
+          v.w = oacc[a][g4 * 4 + 3] * a0 + mine[(2 + a * 16 + g4 * 4 + 3) * 64] * a1;
+          *(float4*)(ps + 256 + ((size_t)(a * 8 + g4 * 2 + lg) * 128 + ql) * 4) = v;
+        }
+    } else if (qi < S) {
+      const float inv = 1.f / lall;
+      const float w0 = a0 * inv, w1 = a1 * inv;
       // O[q][head*HD + c] = O^T[c][q] ; lane holds 4 consecutive c per register quad
       bf16_t* o = out + qi * ldo + (int64_t)head * HD;
 #pragma unroll
@@ -277,12 +311,58 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
   }
 }
 
+// Combines the key ranges of the split work ids: O = sum_i 2^(m_i - m) O_i / sum_i 2^(m_i - m) l_i with
+// m = max_i m_i.  One thread per (query, 4 channels); thread order follows the partial layout.
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ partial, int n_full, int n_tail,
+                                                    int parts, int qblocks, int64_t S,
+                                                    bf16_t* __restrict__ out, int64_t ldo) {
+  constexpr int PER = 128 * (HD / 4);
+  const int g = (int)blockIdx.x * 256 + (int)threadIdx.x;
+  const int j = g / PER, r = g % PER;
+  if (j >= n_tail) return;
+  const int c4 = r >> 7, ql = r & 127;
+  const int wid = n_full + j, head = wid / qblocks;
+  const int64_t qi = (int64_t)(wid % qblocks) * 128 + ql;
+  if (qi >= S) return;
+  const float* ps = partial + (size_t)j * parts * (256 + 128 * HD);
+  float m = -INFINITY;
+  for (int i = 0; i < parts; ++i) m = fmaxf(m, ps[(size_t)i * (256 + 128 * HD) + ql]);
+  float l = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+  for (int i = 0; i < parts; ++i) {
+    const float* pi = ps + (size_t)i * (256 + 128 * HD);
+    const float w = __builtin_amdgcn_exp2f(pi[ql] - m);
+    const float4 v = *(const float4*)(pi + 256 + ((size_t)c4 * 128 + ql) * 4);
+    l += w * pi[128 + ql];
+    o0 += w * v.x; o1 += w * v.y; o2 += w * v.z; o3 += w * v.w;
+  }
+  const float inv = 1.f / l;
+  uint2 pk;
+  pk.x = cvt_pk_bf16(o0 * inv, o1 * inv);
+  pk.y = cvt_pk_bf16(o2 * inv, o3 * inv);
+  *(uint2*)(out + qi * ldo + (int64_t)head * HD + c4 * 4) = pk;
+}
+
+size_t attn_bf16_scratch_bytes(int d) { return (size_t)256 * (256 + 128 * (size_t)d) * sizeof(float); }
+
 void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
                       int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
-                      int h, int d, bf16_t* out, int64_t ldo, hipStream_t st) {
+                      int h, int d, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st) {
   if (S <= 0 || L <= 0) return;
   const int qblocks = (int)((S + 127) / 128);
-  dim3 grid((unsigned)((qblocks * h + 7) / 8 * 8));
+  // One block fits per compute unit, so the grid runs in rounds of 256 blocks.  Whole rounds keep one
+  // block per work id; the work ids left over for the last round are cut into key ranges (at least 8
+  // key tiles each) so that the round is both shorter and wider, and a merge kernel joins the ranges.
+  const int W = qblocks * h, NKT = (int)((L + 63) / 64);
+  const int n_full = W / 256 * 256, n_tail = W - n_full;
+  int parts = 1;
+  if (n_tail > 0 && scratch) {
+    parts = 256 / n_tail;
+    if (parts > 8) parts = 8;
+    if (parts > NKT / 8) parts = NKT / 8;
+    if (parts < 1) parts = 1;
+  }
+  dim3 grid((unsigned)(n_full + (n_tail * parts + 7) / 8 * 8));
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)k_attn_bf16<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16);
@@ -290,7 +370,13 @@ void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, i
     attr_done = true;
   }
   if (d == 128)
-    k_attn_bf16<128><<<grid, 512, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, h);
+    k_attn_bf16<128><<<grid, 512, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch);
   else
-    k_attn_bf16<64><<<grid, 512, 2 * (2 * 64 * 8 + 2 * 64 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, h);
+    k_attn_bf16<64><<<grid, 512, 2 * (2 * 64 * 8 + 2 * 64 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch);
+  if (parts > 1) {
+    const int64_t threads = (int64_t)n_tail * 128 * (d / 4);
+    const unsigned mg = (unsigned)((threads + 255) / 256);
+    if (d == 128) k_attn_merge<128><<<mg, 256, 0, st>>>(scratch, n_full, n_tail, parts, qblocks, S, out, ldo);
+    else k_attn_merge<64><<<mg, 256, 0, st>>>(scratch, n_full, n_tail, parts, qblocks, S, out, ldo);
+  }
 }

@@ -70,7 +70,10 @@ void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ld
 // q must already be multiplied by log2(e)/sqrt(d) (attn_bf16_q_scale) and be readable for
 // roundup(S, 256) rows per head; k rows / vt columns readable (finite in vt) up to
 // k_row0 + roundup(L, 64).
+// scratch: attn_bf16_scratch_bytes(d) bytes of device memory for the partial results of work that is
+// split over key ranges (contents need not be kept between calls), or nullptr to never split.
 inline float attn_bf16_q_scale(int d) { return 1.4426950408889634f / sqrtf((float)d); }
+size_t attn_bf16_scratch_bytes(int d);
 void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
                       int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
-                      int h, int d, bf16_t* out, int64_t ldo, hipStream_t st);
+                      int h, int d, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st);

@@ -64,6 +64,7 @@ struct dp_stage {
   float *tau, *e1, *e2, *e0, *mtab, *mod;
   float2 *rope_f, *rope_y, *rope_x; RopeTables rt;
   void* tap_attn; float *tap_xself, *tap_xcross;
+  float* attn_scratch;
   // state
   int64_t cache_len = 0, last_S = 0; int last_frames = 0;
 };
@@ -152,6 +153,7 @@ static size_t carve(dp_stage* s, void* base) {
     m.tk = cv.take(s->Ltpad * D * E); m.tvt = cv.take(s->Ltpad * D * E);
   }
   const size_t zero_end = cv.off;      // everything up to here is zero-filled at init
+  s->attn_scratch = bf ? (float*)cv.take(attn_bf16_scratch_bytes(c.head_dim)) : nullptr;
   if (bf) {
     for (int64_t l = 0; l < L; ++l) {
       LayerMem& m = s->lm[(size_t)l];
@@ -187,7 +189,8 @@ template <> struct Path<float> {
     launch_gemm_f32((const float*)A, lda, (const float*)W, N, M, N, K, epi, e, st);
   }
   static void attn(const void* q, int64_t qhs, const void* k, int64_t khs, int64_t row0, const void* vt,
-                   int64_t vrs, int64_t S, int64_t L, int h, int d, void* out, int64_t ldo, hipStream_t st) {
+                   int64_t vrs, int64_t S, int64_t L, int h, int d, void* out, int64_t ldo, float* /*scratch*/,
+                   hipStream_t st) {
     launch_attn_f32((const float*)q, qhs, (const float*)k, khs, row0, (const float*)vt, vrs, S, L, h, d, (float*)out, ldo, st);
   }
 };
@@ -198,8 +201,9 @@ template <> struct Path<bf16_t> {
     launch_gemm_bf16((const bf16_t*)A, lda, (const bf16_t*)wt, K, M, N, K, epi, e, st);
   }
   static void attn(const void* q, int64_t qhs, const void* k, int64_t khs, int64_t row0, const void* vt,
-                   int64_t vrs, int64_t S, int64_t L, int h, int d, void* out, int64_t ldo, hipStream_t st) {
-    launch_attn_bf16((const bf16_t*)q, qhs, (const bf16_t*)k, khs, row0, (const bf16_t*)vt, vrs, S, L, h, d, (bf16_t*)out, ldo, st);
+                   int64_t vrs, int64_t S, int64_t L, int h, int d, void* out, int64_t ldo, float* scratch,
+                   hipStream_t st) {
+    launch_attn_bf16((const bf16_t*)q, qhs, (const bf16_t*)k, khs, row0, (const bf16_t*)vt, vrs, S, L, h, d, (bf16_t*)out, ldo, scratch, st);
   }
 };
 
@@ -340,7 +344,7 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
          launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, s->Ncmax, st));
     PROF(DP_PROF_SELF_ATTN,
          Path<T>::attn(s->qbuf, s->Spad * d, m.kbuf, kv_hs, s->Ncmax - s->cache_len, m.vtbuf, s->Lpad, S,
-                       s->cache_len + S, h, d, s->attn_o, D, st));
+                       s->cache_len + S, h, d, s->attn_o, D, s->attn_scratch, st));
     if (s->tap_attn && l == c.n_layers - 1) launch_copy2d<T>((const T*)s->attn_o, 0, (T*)s->tap_attn, 0, 1, S * D, st);
     PROF(DP_PROF_OPROJ_GEMM, Path<T>::gemm(s->attn_o, D, w.wo, m.wo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.bo, g1), st));
     if (s->tap_xself && l == c.n_layers - 1) launch_copy2d<float>(s->xres, 0, s->tap_xself, 0, 1, S * D, st);
@@ -351,7 +355,7 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
          const NormRopeJob<T> cq{0, m.cgq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, 0};
          launch_norm_rope<T>((const T*)s->raw, D, S, h, d, c.eps, &cq, 1, nullptr, 0, 1, 1, st));
     PROF(DP_PROF_CROSS_ATTN,
-         Path<T>::attn(s->qbuf, s->Spad * d, m.tk, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, st));
+         Path<T>::attn(s->qbuf, s->Spad * d, m.tk, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, s->attn_scratch, st));
     PROF(DP_PROF_CROSS_O_GEMM, Path<T>::gemm(s->attn_o, D, w.cwo, m.cwo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.cbo, nullptr), st));
     if (s->tap_xcross && l == c.n_layers - 1) launch_copy2d<float>(s->xres, 0, s->tap_xcross, 0, 1, S * D, st);
     // --- FFN

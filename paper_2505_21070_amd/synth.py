@@ -26,6 +26,10 @@ CONFIGS = {
     # a small ragged bf16 case: head_dim 128, token counts that are not tile multiples, text MLP present
     "small_bf16": dict(n_layers=2, dim=256, n_heads=2, head_dim=128, ffn_dim=640, text_len=40, text_dim=192,
                        tok_h=6, tok_w=12, block_frames=3, cache_frames=2, dtype="bf16"),
+    # few queries against a long ragged key range (31.5 key tiles): the attention grid is small enough
+    # that its work is cut into key ranges which a second kernel merges
+    "longkv_bf16": dict(n_layers=1, dim=128, n_heads=2, head_dim=64, ffn_dim=256, text_len=24, text_dim=128,
+                        tok_h=16, tok_w=21, block_frames=3, cache_frames=3, dtype="bf16"),
     # Wan-1.3B-shaped stage: 4 of 30 layers, 4 frames x 30x52 tokens + 2 cached frames
     "wan1p3b_stage": dict(n_layers=4, dim=1536, n_heads=12, head_dim=128, ffn_dim=8960, text_len=512,
                           text_dim=4096, tok_h=30, tok_w=52, block_frames=4, cache_frames=2, dtype="bf16"),
