@@ -18,11 +18,17 @@
 // block whose row sums end up beyond 2^100 (or non-finite) is recomputed by the safe pass, the classical
 // online softmax that raises m whenever a tile exceeds it and rescales O^T.
 //
-// Work split: a block of 8 wavefronts owns 128 queries of one head; wavefront w handles query tile
-// w & 3 (32 queries) against key group w >> 2 (first / second half of the key tiles).  The two groups
-// stream their own K / V^T tiles (64 keys, double-buffered, loaded HBM -> LDS directly) and are merged
-// through LDS at the end.  Two wavefronts per SIMD hide each other's LDS and matrix-core latencies; the
-// key split halves the length of a block so that the tail of the grid wastes less of the machine.
+// Work split: a block of 8 wavefronts owns QG * 32 queries of one head.  Two shapes are built.
+// QG = 4, KG = 2 (short key ranges, i.e. cross-attention): wavefront w handles query tile w & 3 against
+// key group w >> 2 (first / second half of the key tiles); the two groups stream their own K / V^T tiles
+// and are merged through LDS at the end, which halves the length of a block.  QG = 8, KG = 1 (long key
+// ranges): all 8 wavefronts share every K / V^T tile, so a tile brought into LDS serves 256 queries and
+// the LDS fill traffic per query halves.  Tiles hold 64 keys, are double-buffered and are loaded
+// HBM -> LDS directly.  Two wavefronts per SIMD hide each other's LDS and matrix-core latencies.
+//
+// Grid: one block fits per compute unit, so a grid runs in rounds of 256 blocks.  The work ids that
+// would make up a last, partly filled round are instead cut into several key ranges each, one block per
+// range, which write unnormalised partial results (m, l, O) to a scratch buffer; k_attn_merge joins them.
 #include <type_traits>
 
 #include "kernels.h"
@@ -49,7 +55,7 @@ template <int CR> __device__ __forceinline__ int kswz(int row) { return CR == 16
 // tile row -> key held in that row: bits 2 and 3 of the row index are exchanged
 __device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
-template <int HD>
+template <int HD, int QG, int KG>
 __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q, int64_t q_head_stride,
                                                   const bf16_t* __restrict__ k, int64_t k_head_stride,
                                                   int64_t k_row0, const bf16_t* __restrict__ vt,
@@ -62,13 +68,16 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
   constexpr int DT = HD / 32;                // 32-row tiles of O^T
   constexpr int KCH = 64 * CR;               // chunks in a K tile
   constexpr int VCH = HD * 8;                // chunks in a V^T tile
-  constexpr int GCH = 2 * KCH + 2 * VCH;     // chunks per key group: K tiles 0/1, V^T tiles 0/1
-  constexpr int CK = KCH / 256, CV = VCH / 256;
-  extern __shared__ uint4 smem[];            // 2 * GCH chunks
+  constexpr int NBUF = 2;                    // tile buffers per key group (a third one was measured: no gain)
+  constexpr int GCH = NBUF * (KCH + VCH);    // chunks per key group: NBUF K tiles, NBUF V^T tiles
+  constexpr int CK = KCH / (QG * 64), CV = VCH / (QG * 64);   // load instructions per wavefront and tile
+  constexpr int QB = QG * 32;                // queries per block
+  static_assert(QG * KG == 8, "8 wavefronts");
+  extern __shared__ uint4 smem[];            // KG * GCH chunks
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int qt = wave & 3, kg = wave >> 2;
+  const int qt = wave % QG, kg = wave / QG;
   const int lr = lane & 31, lg = lane >> 5;
   // Blocks are dealt round-robin over the 8 XCDs, each with its own L2: give every XCD a contiguous run
   // of (head, query block) work ids so that the blocks streaming one head's K/V share an L2.  The first
@@ -92,12 +101,12 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
     }
   }
   const int head = wid / qblocks;
-  const int64_t q0 = (int64_t)(wid % qblocks) * 128 + qt * 32;
+  const int64_t q0 = (int64_t)(wid % qblocks) * QB + qt * 32;
   uint4* const kbuf = smem + kg * GCH;
-  uint4* const vbuf = kbuf + 2 * KCH;
+  uint4* const vbuf = kbuf + NBUF * KCH;
 
   // this wavefront's share of the key tiles
-  const int n0 = (t1 - t0 + 1) / 2;                   // tiles of group 0; also the trip count for everyone
+  const int n0 = KG == 2 ? (t1 - t0 + 1) / 2 : t1 - t0;   // tiles of group 0; also the trip count for everyone
   const int first = t0 + (kg ? n0 : 0), cnt = kg ? t1 - t0 - n0 : n0;
 
   // Q fragments stay in registers: B operand, column = query, 8 head-dim values per lane
@@ -117,12 +126,12 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
   int koff[CK], voff[CV];
 #pragma unroll
   for (int i = 0; i < CK; ++i) {
-    const int p = qt * (KCH / 4) + i * 64 + lane, row = p / CR, ch = (p % CR) ^ kswz<CR>(row);
+    const int p = qt * (KCH / QG) + i * 64 + lane, row = p / CR, ch = (p % CR) ^ kswz<CR>(row);
     koff[i] = swap23(row) * HD + ch * 8;
   }
 #pragma unroll
   for (int i = 0; i < CV; ++i) {
-    const int p = qt * (VCH / 4) + i * 64 + lane, row = p >> 3, ch = (p & 7) ^ ((row >> 1) & 7);
+    const int p = qt * (VCH / QG) + i * 64 + lane, row = p >> 3, ch = (p & 7) ^ ((row >> 1) & 7);
     voff[i] = row * (int)vt_row_stride + ch * 8;
   }
   auto load_tile = [&](int tile, int bufi) __attribute__((always_inline)) {
@@ -131,11 +140,11 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
 #pragma unroll
     for (int i = 0; i < CK; ++i)
       __builtin_amdgcn_global_load_lds((glb_void_t*)(ks_ + koff[i]),
-                                       (lds_void_t*)(kbuf + bufi * KCH + qt * (KCH / 4) + i * 64), 16, 0, 0);
+                                       (lds_void_t*)(kbuf + bufi * KCH + qt * (KCH / QG) + i * 64), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < CV; ++i)
       __builtin_amdgcn_global_load_lds((glb_void_t*)(vs_ + voff[i]),
-                                       (lds_void_t*)(vbuf + bufi * VCH + qt * (VCH / 4) + i * 64), 16, 0, 0);
+                                       (lds_void_t*)(vbuf + bufi * VCH + qt * (VCH / QG) + i * 64), 16, 0, 0);
   };
 
   f32x16 oacc[DT], negm;
@@ -179,9 +188,9 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
       if (kt < cnt) {
         // next tile into the other buffer (read last before the previous barrier); the tile past the
         // end is the last one again and never used
-        load_tile(kt + 1 < cnt ? kt + 1 : cnt - 1, (kt + 1) & 1);
-        const uint4* kb = kbuf + (kt & 1) * KCH;
-        const uint4* vb = vbuf + (kt & 1) * VCH;
+        load_tile(kt + NBUF - 1 < cnt ? kt + NBUF - 1 : cnt - 1, (kt + NBUF - 1) % NBUF);
+        const uint4* kb = kbuf + (kt % NBUF) * KCH;
+        const uint4* vb = vbuf + (kt % NBUF) * VCH;
         const int kvalid = (int)(L - (int64_t)(first + kt) * 64);     // < 64 only in the ragged last tile
 #pragma unroll
         for (int a = 0; a < 2; ++a) {                                  // two 32-key halves of the tile
@@ -257,38 +266,49 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
   // merge the two key groups through LDS (tile buffers are free now): group 1 publishes m, l, O^T
   float* xch = (float*)smem;                           // [qt][DT*16 + 2][64 lanes]
   float* mine = xch + (size_t)qt * (DT * 16 + 2) * 64 + lane;
-  if (kg == 1) {
-    mine[0] = empty ? -INFINITY : mrun;
-    mine[64] = ltot;
+  if constexpr (KG == 2) {
+    if (kg == 1) {
+      mine[0] = empty ? -INFINITY : mrun;
+      mine[64] = ltot;
 #pragma unroll
-    for (int a = 0; a < DT; ++a)
+      for (int a = 0; a < DT; ++a)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mine[(2 + a * 16 + r) * 64] = oacc[a][r];
+        for (int r = 0; r < 16; ++r) mine[(2 + a * 16 + r) * 64] = oacc[a][r];
+    }
+    __syncthreads();
   }
-  __syncthreads();
   if (kg == 0) {
-    const float m1 = mine[0], l1 = mine[64];
-    const float m0 = empty ? -INFINITY : mrun;
-    const float m = fmaxf(m0, m1);
-    const float a0 = __builtin_amdgcn_exp2f(m0 - m), a1 = __builtin_amdgcn_exp2f(m1 - m);   // 2^-inf = 0
-    const float lall = ltot * a0 + l1 * a1;
+    float m = mrun, a0 = 1.f, a1 = 0.f, lall = ltot;
+    if constexpr (KG == 2) {
+      const float m1 = mine[0], l1 = mine[64];
+      const float m0 = empty ? -INFINITY : mrun;
+      m = fmaxf(m0, m1);
+      a0 = __builtin_amdgcn_exp2f(m0 - m); a1 = __builtin_amdgcn_exp2f(m1 - m);   // 2^-inf = 0
+      lall = ltot * a0 + l1 * a1;
+    }
+    // this lane's O^T value (register r of channel tile a) over both key groups, scaled by w0 / w1
+    auto both = [&](int a, int r, float w0, float w1) __attribute__((always_inline)) {
+      float v = oacc[a][r] * w0;
+      if constexpr (KG == 2) v += mine[(2 + a * 16 + r) * 64] * w1;
+      return v;
+    };
     const int64_t qi = q0 + lr;
     if (slot >= 0) {
       // one key range of a split work id: publish m, l and the unnormalised O^T for the merge kernel.
-      // Slot layout (floats): m[128], l[128], then O as [HD/4][128 queries][4 channels].
-      float* ps = partial + (size_t)slot * (256 + 128 * HD);
+      // Slot layout (floats): m[QB], l[QB], then O as [HD/4][QB queries][4 channels].
+      float* ps = partial + (size_t)slot * (2 * QB + QB * HD);
       const int ql = qt * 32 + lr;
-      if (lg == 0) { ps[ql] = m; ps[128 + ql] = lall; }
+      if (lg == 0) { ps[ql] = m; ps[QB + ql] = lall; }
 #pragma unroll
       for (int a = 0; a < DT; ++a)
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
           float4 v;
-          v.x = oacc[a][g4 * 4 + 0] * a0 + mine[(2 + a * 16 + g4 * 4 + 0) * 64] * a1;
-          v.y = oacc[a][g4 * 4 + 1] * a0 + mine[(2 + a * 16 + g4 * 4 + 1) * 64] * a1;
-          v.z = oacc[a][g4 * 4 + 2] * a0 + mine[(2 + a * 16 + g4 * 4 + 2) * 64] * a1;
-          v.w = oacc[a][g4 * 4 + 3] * a0 + mine[(2 + a * 16 + g4 * 4 + 3) * 64] * a1;
-          *(float4*)(ps + 256 + ((size_t)(a * 8 + g4 * 2 + lg) * 128 + ql) * 4) = v;
+          v.x = both(a, g4 * 4 + 0, a0, a1);
+          v.y = both(a, g4 * 4 + 1, a0, a1);
+          v.z = both(a, g4 * 4 + 2, a0, a1);
+          v.w = both(a, g4 * 4 + 3, a0, a1);
+          *(float4*)(ps + 2 * QB + ((size_t)(a * 8 + g4 * 2 + lg) * QB + ql) * 4) = v;
         }
     } else if (qi < S) {
       const float inv = 1.f / lall;
@@ -299,12 +319,9 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
       for (int a = 0; a < DT; ++a)
 #pragma unroll
         for (int g4 = 0; g4 < 4; ++g4) {
-          float v[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) v[j] = oacc[a][g4 * 4 + j] * w0 + mine[(2 + a * 16 + g4 * 4 + j) * 64] * w1;
           uint2 pk;
-          pk.x = cvt_pk_bf16(v[0], v[1]);
-          pk.y = cvt_pk_bf16(v[2], v[3]);
+          pk.x = cvt_pk_bf16(both(a, g4 * 4 + 0, w0, w1), both(a, g4 * 4 + 1, w0, w1));
+          pk.y = cvt_pk_bf16(both(a, g4 * 4 + 2, w0, w1), both(a, g4 * 4 + 3, w0, w1));
           *(uint2*)(o + a * 32 + g4 * 8 + lg * 4) = pk;
         }
     }
@@ -313,27 +330,27 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
 
 // Combines the key ranges of the split work ids: O = sum_i 2^(m_i - m) O_i / sum_i 2^(m_i - m) l_i with
 // m = max_i m_i.  One thread per (query, 4 channels); thread order follows the partial layout.
-template <int HD>
+template <int HD, int QB>
 __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ partial, int n_full, int n_tail,
                                                     int parts, int qblocks, int64_t S,
                                                     bf16_t* __restrict__ out, int64_t ldo) {
-  constexpr int PER = 128 * (HD / 4);
+  constexpr int PER = QB * (HD / 4), SLOT = 2 * QB + QB * HD;
   const int g = (int)blockIdx.x * 256 + (int)threadIdx.x;
   const int j = g / PER, r = g % PER;
   if (j >= n_tail) return;
-  const int c4 = r >> 7, ql = r & 127;
+  const int c4 = r / QB, ql = r % QB;
   const int wid = n_full + j, head = wid / qblocks;
-  const int64_t qi = (int64_t)(wid % qblocks) * 128 + ql;
+  const int64_t qi = (int64_t)(wid % qblocks) * QB + ql;
   if (qi >= S) return;
-  const float* ps = partial + (size_t)j * parts * (256 + 128 * HD);
+  const float* ps = partial + (size_t)j * parts * SLOT;
   float m = -INFINITY;
-  for (int i = 0; i < parts; ++i) m = fmaxf(m, ps[(size_t)i * (256 + 128 * HD) + ql]);
+  for (int i = 0; i < parts; ++i) m = fmaxf(m, ps[(size_t)i * SLOT + ql]);
   float l = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
   for (int i = 0; i < parts; ++i) {
-    const float* pi = ps + (size_t)i * (256 + 128 * HD);
+    const float* pi = ps + (size_t)i * SLOT;
     const float w = __builtin_amdgcn_exp2f(pi[ql] - m);
-    const float4 v = *(const float4*)(pi + 256 + ((size_t)c4 * 128 + ql) * 4);
-    l += w * pi[128 + ql];
+    const float4 v = *(const float4*)(pi + 2 * QB + ((size_t)c4 * QB + ql) * 4);
+    l += w * pi[QB + ql];
     o0 += w * v.x; o1 += w * v.y; o2 += w * v.z; o3 += w * v.w;
   }
   const float inv = 1.f / l;
@@ -343,13 +360,16 @@ __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ pa
   *(uint2*)(out + qi * ldo + (int64_t)head * HD + c4 * 4) = pk;
 }
 
-size_t attn_bf16_scratch_bytes(int d) { return (size_t)256 * (256 + 128 * (size_t)d) * sizeof(float); }
+// partial results of at most 256 blocks of at most 256 queries
+size_t attn_bf16_scratch_bytes(int d) { return (size_t)256 * (512 + 256 * (size_t)d) * sizeof(float); }
 
-void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
-                      int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
-                      int h, int d, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st) {
-  if (S <= 0 || L <= 0) return;
-  const int qblocks = (int)((S + 127) / 128);
+template <int HD, int QG, int KG>
+static void launch_attn_cfg(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
+                            int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
+                            int h, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st) {
+  constexpr int QB = QG * 32;
+  constexpr int lds = KG * 2 * (64 * (HD / 8) + HD * 8) * 16;
+  const int qblocks = (int)((S + QB - 1) / QB);
   // One block fits per compute unit, so the grid runs in rounds of 256 blocks.  Whole rounds keep one
   // block per work id; the work ids left over for the last round are cut into key ranges (at least 8
   // key tiles each) so that the round is both shorter and wider, and a merge kernel joins the ranges.
@@ -365,18 +385,25 @@ void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, i
   dim3 grid((unsigned)(n_full + (n_tail * parts + 7) / 8 * 8));
   static bool attr_done = false;
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_attn_bf16<128>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16);
-    (void)hipFuncSetAttribute((const void*)k_attn_bf16<64>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * (2 * 64 * 8 + 2 * 64 * 8) * 16);
+    (void)hipFuncSetAttribute((const void*)k_attn_bf16<HD, QG, KG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     attr_done = true;
   }
-  if (d == 128)
-    k_attn_bf16<128><<<grid, 512, 2 * (2 * 64 * 16 + 2 * 128 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch);
-  else
-    k_attn_bf16<64><<<grid, 512, 2 * (2 * 64 * 8 + 2 * 64 * 8) * 16, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch);
+  k_attn_bf16<HD, QG, KG><<<grid, 512, lds, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch);
   if (parts > 1) {
-    const int64_t threads = (int64_t)n_tail * 128 * (d / 4);
-    const unsigned mg = (unsigned)((threads + 255) / 256);
-    if (d == 128) k_attn_merge<128><<<mg, 256, 0, st>>>(scratch, n_full, n_tail, parts, qblocks, S, out, ldo);
-    else k_attn_merge<64><<<mg, 256, 0, st>>>(scratch, n_full, n_tail, parts, qblocks, S, out, ldo);
+    const int64_t threads = (int64_t)n_tail * QB * (HD / 4);
+    k_attn_merge<HD, QB><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(scratch, n_full, n_tail, parts, qblocks, S, out, ldo);
   }
+}
+
+void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
+                      int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
+                      int h, int d, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st) {
+  if (S <= 0 || L <= 0) return;
+  // Long key ranges: 256 queries per block share every K / V^T tile (half the LDS fill traffic per
+  // query).  Short ones (cross-attention): 128 queries per block with the keys split over two groups.
+  const bool wide = L >= 2048 && ((S + 255) / 256) * h >= 128;
+#define ATTN_ARGS q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, h, out, ldo, scratch, st
+  if (d == 128) { if (wide) launch_attn_cfg<128, 8, 1>(ATTN_ARGS); else launch_attn_cfg<128, 4, 2>(ATTN_ARGS); }
+  else { if (wide) launch_attn_cfg<64, 8, 1>(ATTN_ARGS); else launch_attn_cfg<64, 4, 2>(ATTN_ARGS); }
+#undef ATTN_ARGS
 }

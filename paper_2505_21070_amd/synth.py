@@ -30,6 +30,10 @@ CONFIGS = {
     # that its work is cut into key ranges which a second kernel merges
     "longkv_bf16": dict(n_layers=1, dim=128, n_heads=2, head_dim=64, ffn_dim=256, text_len=24, text_dim=128,
                         tok_h=16, tok_w=21, block_frames=3, cache_frames=3, dtype="bf16"),
+    # enough (head, 256-query block) pairs and keys for the attention kernel's 256-query block shape at
+    # head_dim 64, with its work ids cut into two key ranges
+    "wide64_bf16": dict(n_layers=1, dim=1024, n_heads=16, head_dim=64, ffn_dim=1024, text_len=32, text_dim=1024,
+                        tok_h=16, tok_w=16, block_frames=8, cache_frames=2, dtype="bf16"),
     # Wan-1.3B-shaped stage: 4 of 30 layers, 4 frames x 30x52 tokens + 2 cached frames
     "wan1p3b_stage": dict(n_layers=4, dim=1536, n_heads=12, head_dim=128, ffn_dim=8960, text_len=512,
                           text_dim=4096, tok_h=30, tok_w=52, block_frames=4, cache_frames=2, dtype="bf16"),
