@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0         # HBM3E, published
 # HBM-side bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this command
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for the plain cache-copy kernel of
 # known size; figures and commands in profiles/bench_wan1p3b_stage.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 206.8e6}
+MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 233.6e6}
 
 
 def class_work(cfg, S, Nc):
@@ -207,6 +207,9 @@ def main():
         "all_gemm_attn_tflops": all_flops / (all_ms * 1e-3) / 1e12 if all_ms else None,
         "breakdown": breakdown,
     }
+    if cfg["dtype"] == "bf16":
+        # what the matrix cores sustain on this machine with nothing else running: zero vs pseudo-random operand bits
+        res["mfma_issue_ceiling_tflops"] = {"zeros": B.probe_mfma_bf16("zeros"), "random": B.probe_mfma_bf16("random")}
     if not args.no_cpu_baseline and not queue:
         res["cpu_baseline"] = cpu_baseline(cfg, weights, text, blocks[1])
     print(json.dumps(res))

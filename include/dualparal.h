@@ -186,6 +186,18 @@ int dp_stage_profile_begin(dp_stage_t* stage, uint32_t class_mask);
 int dp_stage_profile_end(dp_stage_t* stage, double* ms /* host [DP_PROF_COUNT] */,
                          int64_t* launches /* host [DP_PROF_COUNT] */);
 
+/* Measurement aid: the rate (TFLOP/s) at which the GPU issues bf16 32x32x16 MFMAs when nothing else
+ * happens, 2 wavefronts per SIMD on every compute unit, for all-zero or pseudo-random operand bits.  The
+ * clock under matrix load depends on operand bit activity, so the attainable ceiling for real data is
+ * below the one for zeros; roofline fractions against the published peak are read next to this figure.
+ *   iters         : MFMAs per accumulator (4 accumulators per wavefront); 20000 runs a few milliseconds
+ *   scratch       : device buffer of at least 131072 floats that the kernel overwrites
+ *   tflops        : host; receives the measured rate
+ * Synchronises the stream.  Errors: DP_EINVAL, DP_EHIP. */
+enum { DP_PROBE_ZEROS = 0, DP_PROBE_RANDOM = 1 };
+int dp_probe_mfma_bf16(int32_t operand_mode, int32_t iters, float* scratch, int64_t scratch_floats,
+                       void* hip_stream, double* tflops);
+
 /* Releases the host-side handle (device memory belongs to the caller).  NULL is allowed. */
 void dp_stage_free(dp_stage_t* stage);
 

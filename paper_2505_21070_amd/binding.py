@@ -75,6 +75,8 @@ _lib.dp_stage_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
 _lib.dp_stage_profile_end.restype = C.c_int
 _lib.dp_stage_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 _lib.dp_stage_free.restype = None
+_lib.dp_probe_mfma_bf16.restype = C.c_int
+_lib.dp_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_double)]
 _lib.dp_stage_free.argtypes = [C.c_void_p]
 _lib.dp_last_error.restype = C.c_char_p
 _lib.dp_last_error.argtypes = []
@@ -223,6 +225,16 @@ def blockwise_schedule(T, block_num, num_b, num_c, first_block_frames=0, t_max=1
 
 def bubble_ratio(n_devices, T, block_num, order="reverse"):
     return float(_lib.dp_bubble_ratio(n_devices, T, block_num, ORDER[order]))
+
+
+def probe_mfma_bf16(operands="random", iters=20000, device="cuda"):
+    """Rate (TFLOP/s) of back-to-back bf16 MFMAs with all-zero or pseudo-random operand bits."""
+    scratch = torch.empty(131072, dtype=torch.float32, device=device)
+    out = C.c_double()
+    stream = torch.cuda.current_stream().cuda_stream
+    _check(_lib.dp_probe_mfma_bf16({"zeros": 0, "random": 1}[operands], iters, scratch.data_ptr(), scratch.numel(),
+                                   stream, C.byref(out)), "dp_probe_mfma_bf16")
+    return out.value
 
 
 def weights_to_device(weights, dtype, device="cuda"):

@@ -329,16 +329,18 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
 }
 
 // Combines the key ranges of the split work ids: O = sum_i 2^(m_i - m) O_i / sum_i 2^(m_i - m) l_i with
-// m = max_i m_i.  One thread per (query, 4 channels); thread order follows the partial layout.
+// m = max_i m_i.  One thread per (query, 4 channels).  A block of 256 threads covers all channels of
+// 256 / (HD/4) consecutive queries (query index fastest), so that partials are read in whole 128-byte
+// lines and every output row is written from one block.
 template <int HD, int QB>
 __global__ __launch_bounds__(256) void k_attn_merge(const float* __restrict__ partial, int n_full, int n_tail,
                                                     int parts, int qblocks, int64_t S,
                                                     bf16_t* __restrict__ out, int64_t ldo) {
-  constexpr int PER = QB * (HD / 4), SLOT = 2 * QB + QB * HD;
-  const int g = (int)blockIdx.x * 256 + (int)threadIdx.x;
-  const int j = g / PER, r = g % PER;
+  constexpr int C4 = HD / 4, QPB = 256 / C4, SLOT = 2 * QB + QB * HD;
+  const int tid = (int)threadIdx.x;
+  const int gq = (int)blockIdx.x * QPB + tid % QPB;      // query index over all split work ids
+  const int j = gq / QB, ql = gq % QB, c4 = tid / QPB;
   if (j >= n_tail) return;
-  const int c4 = r / QB, ql = r % QB;
   const int wid = n_full + j, head = wid / qblocks;
   const int64_t qi = (int64_t)(wid % qblocks) * QB + ql;
   if (qi >= S) return;
@@ -390,8 +392,8 @@ static void launch_attn_cfg(const bf16_t* q, int64_t q_head_stride, const bf16_t
   }
   k_attn_bf16<HD, QG, KG><<<grid, 512, lds, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch);
   if (parts > 1) {
-    const int64_t threads = (int64_t)n_tail * QB * (HD / 4);
-    k_attn_merge<HD, QB><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(scratch, n_full, n_tail, parts, qblocks, S, out, ldo);
+    constexpr int QPB = 256 / (HD / 4);                  // queries per merge block
+    k_attn_merge<HD, QB><<<(unsigned)(n_tail * (QB / QPB)), 256, 0, st>>>(scratch, n_full, n_tail, parts, qblocks, S, out, ldo);
   }
 }
 
