@@ -106,7 +106,7 @@ def main():
     # of the queue tail to head (8 block passes, each reading the cache of the pass before it)
     queue = args.workload == "wan1p3b_queue"
     cfg, weights, text, blocks = synth.make_case("wan1p3b_full" if queue else args.workload, seed=0,
-                                                 n_blocks=8 if queue else 2)
+                                                 n_blocks=2)
     nf, nc, tok = cfg["block_frames"], cfg["cache_frames"], cfg["tok_h"] * cfg["tok_w"]
     S, Nc = nf * tok, nc * tok
     td = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
@@ -121,9 +121,15 @@ def main():
     torch.cuda.synchronize()
 
     if queue:
-        xq = [b.to("cuda", td).contiguous() for b in blocks]
-        sweep = [e for e in B.blockwise_schedule(8, 8, nf, 2 * nc, 0, 1000.0, "reverse") if e["step"] == 8]
-        assert len(sweep) == 8
+        # 9 blocks initialised from the shared noise pool (coordinated noise initialisation: block 1 is the
+        # whole pool of nf + nc frames); the sweep timed is diffusion step 9 of T = 8, when blocks 9..2, all
+        # nf frames long, fill the queue
+        gen = torch.Generator().manual_seed(1)
+        pool = synth.noise_pool(cfg, nf + nc, gen).to("cuda", td).contiguous()
+        idx = B.noise_assign(9, nf, 2 * nc, synth.shuffle_words(8 * (nf - 1), 2))
+        xq = [B.noise_gather(pool, torch.tensor(i, dtype=torch.int32, device="cuda")).reshape(-1, cfg["dim"]) for i in idx]
+        sweep = [e for e in B.blockwise_schedule(8, 9, nf, 2 * nc, nf + nc, 1000.0, "reverse") if e["step"] == 9]
+        assert len(sweep) == 8 and all(e["n_frames"] == nf for e in sweep)
 
         def step():
             for e in sweep:

@@ -158,6 +158,39 @@ int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry* out, int64
  * (N <= block_num / N > block_num), Eq. 5 for DP_ORDER_SEQUENTIAL.  Host only.  Returns -1 on bad input. */
 double dp_bubble_ratio(int32_t n_devices, int32_t T, int32_t block_num, int32_t order);
 
+/*
+ * Coordinated noise initialisation (Sec. 3.3, overview figure): every block's initial noise is taken
+ * from one shared pool of num_b + num_c/2 frame noises.  Block 1 is the whole pool in its stored order
+ * (it is num_c/2 frames longer than the others); each later block is a shuffle of the pool frames that
+ * the last num_c/2 frames of the block before it did not use.
+ *
+ * dp_noise_assign (host only) writes the pool-frame index of every frame of every block, block after
+ * block: num_b + num_c/2 entries for block 1, num_b for each later one.  The shuffle is driven by the
+ * caller's random words: candidates start in ascending pool index; for position i = num_b-1 .. 1 the
+ * entry at i is exchanged with the one at (word mod (i+1)), one word per exchange, consumed in order.
+ *   random_words : host, at least (block_num - 1) * (num_b - 1) words (may be NULL if that is 0)
+ *   pool_index   : host, out; *n_written receives the number of entries.  capacity too small: nothing
+ *                  is written, DP_ENOMEM (pool_index may then be NULL)
+ * Errors: DP_EINVAL (null cfg / n_written, block_num < 1, num_b < 1, num_c < 0, too few words), DP_ENOMEM.
+ *
+ * dp_noise_gather (device) materialises a block's initial noise: out[f, :] = pool[index[f], :].
+ *   pool        : device, [pool_frames, frame_bytes] bytes, 16-byte aligned; frame_bytes % 16 == 0
+ *   index       : device int32 [n_frames]; entries outside [0, pool_frames) make the kernel write
+ *                 zeros for that frame
+ *   out         : device, [n_frames, frame_bytes] bytes, 16-byte aligned, must not overlap pool
+ * Asynchronous on hip_stream.  n_frames <= 65535; n_frames == 0 is a no-op (pointers are not looked at).  Errors: DP_EINVAL (null pointer, negative size, bad
+ * alignment, too many frames).
+ */
+typedef struct {
+  int32_t block_num;          /* blocks in the video                                               */
+  int32_t num_b;              /* frames per block (block 1 has num_b + num_c/2)                    */
+  int32_t num_c;              /* context frames; the pool holds num_b + num_c/2 frame noises       */
+} dp_noise_config;
+int dp_noise_assign(const dp_noise_config* cfg, const uint32_t* random_words, int64_t n_words,
+                    int32_t* pool_index, int64_t capacity, int64_t* n_written);
+int dp_noise_gather(const void* pool, int32_t pool_frames, int64_t frame_bytes, const int32_t* index,
+                    int32_t n_frames, void* out, void* hip_stream);
+
 /* Test hook: copies an internal result to `dst` as float32, token-major [rows, dim].
  *   what : DP_PEEK_*; layer is used by the K / V / cache / modulation peeks, the others refer to the
  *          last layer the last forward ran (they need cfg.debug_taps for X_SELF / X_CROSS).

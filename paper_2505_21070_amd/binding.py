@@ -75,6 +75,15 @@ _lib.dp_stage_profile_begin.argtypes = [C.c_void_p, C.c_uint32]
 _lib.dp_stage_profile_end.restype = C.c_int
 _lib.dp_stage_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 _lib.dp_stage_free.restype = None
+class NoiseConfig(C.Structure):
+    _fields_ = [("block_num", C.c_int32), ("num_b", C.c_int32), ("num_c", C.c_int32)]
+
+
+_lib.dp_noise_assign.restype = C.c_int
+_lib.dp_noise_assign.argtypes = [C.POINTER(NoiseConfig), C.POINTER(C.c_uint32), C.c_int64, C.POINTER(C.c_int32),
+                                 C.c_int64, C.POINTER(C.c_int64)]
+_lib.dp_noise_gather.restype = C.c_int
+_lib.dp_noise_gather.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
 _lib.dp_probe_mfma_bf16.restype = C.c_int
 _lib.dp_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_double)]
 _lib.dp_stage_free.argtypes = [C.c_void_p]
@@ -225,6 +234,33 @@ def blockwise_schedule(T, block_num, num_b, num_c, first_block_frames=0, t_max=1
 
 def bubble_ratio(n_devices, T, block_num, order="reverse"):
     return float(_lib.dp_bubble_ratio(n_devices, T, block_num, ORDER[order]))
+
+
+def noise_assign(block_num, num_b, num_c, words):
+    """Pool-frame indices of every block (list of lists), from the caller's uint32 random words."""
+    cfg = NoiseConfig(block_num, num_b, num_c)
+    w = (C.c_uint32 * max(len(words), 1))(*[int(v) for v in words])
+    n = C.c_int64()
+    rc = _lib.dp_noise_assign(C.byref(cfg), w, len(words), None, 0, C.byref(n))
+    if rc not in (DP_OK, DP_ENOMEM):
+        raise DualParalError(rc, "dp_noise_assign")
+    arr = (C.c_int32 * n.value)()
+    _check(_lib.dp_noise_assign(C.byref(cfg), w, len(words), arr, n.value, C.byref(n)), "dp_noise_assign")
+    flat, first = list(arr), num_b + num_c // 2
+    return [flat[:first]] + [flat[first + i * num_b: first + (i + 1) * num_b] for i in range(block_num - 1)]
+
+
+def noise_gather(pool, index, out=None):
+    """out[f] = pool[index[f]] on the device; pool is [pool_frames, ...], index an int32 device tensor."""
+    assert pool.is_cuda and pool.is_contiguous() and index.is_cuda and index.dtype == torch.int32
+    n = int(index.numel())
+    if out is None:
+        out = torch.empty((n,) + tuple(pool.shape[1:]), dtype=pool.dtype, device=pool.device)
+    frame_bytes = pool[0].numel() * pool.element_size()
+    stream = torch.cuda.current_stream().cuda_stream
+    _check(_lib.dp_noise_gather(pool.data_ptr(), pool.shape[0], frame_bytes, index.data_ptr(), n, out.data_ptr(), stream),
+           "dp_noise_gather")
+    return out
 
 
 def probe_mfma_bf16(operands="random", iters=20000, device="cuda"):

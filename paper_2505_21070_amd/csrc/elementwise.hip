@@ -400,3 +400,26 @@ void launch_gather_vt(const T* vt, int64_t row_stride, int64_t col0, int64_t S, 
 }
 template void launch_gather_vt<float>(const float*, int64_t, int64_t, int64_t, int, int, float*, hipStream_t);
 template void launch_gather_vt<bf16_t>(const bf16_t*, int64_t, int64_t, int64_t, int, int, float*, hipStream_t);
+
+// ---------------------------------------------------------------- coordinated noise initialisation: frame gather
+// out[f, :] = pool[index[f], :] in 16-byte vectors; a frame whose index is out of range is written as zeros
+__global__ __launch_bounds__(256) void k_gather_frames(const uint4* __restrict__ pool, int pool_frames,
+                                                       int64_t frame_vecs, const int32_t* __restrict__ index,
+                                                       uint4* __restrict__ out) {
+  const int f = blockIdx.y;
+  const int src = index[f];
+  const bool ok = src >= 0 && src < pool_frames;
+  const uint4* s = pool + (int64_t)(ok ? src : 0) * frame_vecs;
+  uint4* d = out + (int64_t)f * frame_vecs;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < frame_vecs; i += (int64_t)gridDim.x * 256)
+    d[i] = ok ? s[i] : make_uint4(0, 0, 0, 0);
+}
+void launch_gather_frames(const void* pool, int pool_frames, int64_t frame_bytes, const int32_t* index,
+                          int n_frames, void* out, hipStream_t st) {
+  if (n_frames <= 0 || frame_bytes <= 0) return;
+  const int64_t vecs = frame_bytes / 16;
+  int64_t bx = cdiv(vecs, 256 * 4);                 // 4 vectors per thread
+  if (bx < 1) bx = 1;
+  if (bx > 4096) bx = 4096;
+  k_gather_frames<<<dim3((unsigned)bx, (unsigned)n_frames), 256, 0, st>>>((const uint4*)pool, pool_frames, vecs, index, (uint4*)out);
+}

@@ -62,6 +62,9 @@ void launch_attn_f32(const float* q, int64_t q_head_stride, const float* k, int6
                      int64_t k_row0, const float* vt, int64_t vt_row_stride, int64_t S, int64_t L,
                      int h, int d, float* out, int64_t ldo, hipStream_t st);
 
+// out[f, :] = pool[index[f], :], frame_bytes % 16 == 0, all pointers 16-byte aligned
+void launch_gather_frames(const void* pool, int pool_frames, int64_t frame_bytes, const int32_t* index,
+                          int n_frames, void* out, hipStream_t st);
 // ---- gemm_bf16.hip : C = A[M,K] * Wt[N,K]^T (+ epilogue), bf16 MFMA, fp32 accumulate --------
 // A must be readable for roundup(M, 256) rows, Wt for roundup(N, 256) rows; K % 64 == 0.
 void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M,

@@ -58,3 +58,37 @@ extern "C" double dp_bubble_ratio(int32_t N, int32_t T, int32_t block_num, int32
   else bubble = (double)block_num * (N - T) + (double)N * (T - 2) + 1.0;
   return bubble / (bubble + (double)T * block_num);
 }
+
+// Sec. 3.3: block 1 is the whole pool; a later block is a shuffle of the pool frames that the last
+// num_c/2 frames of the block before it did not use (exactly num_b of them).
+extern "C" int dp_noise_assign(const dp_noise_config* cfg, const uint32_t* random_words, int64_t n_words,
+                               int32_t* pool_index, int64_t capacity, int64_t* n_written) {
+  if (!cfg || !n_written) return dp_set_error(DP_EINVAL, "dp_noise_assign: null pointer");
+  if (cfg->block_num < 1 || cfg->num_b < 1 || cfg->num_c < 0)
+    return dp_set_error(DP_EINVAL, "dp_noise_assign: bad block_num / num_b / num_c");
+  const int32_t nb = cfg->num_b, half = cfg->num_c / 2, pool = nb + half;
+  const int64_t need_words = (int64_t)(cfg->block_num - 1) * (nb - 1);
+  if (n_words < need_words || (need_words > 0 && !random_words))
+    return dp_set_error(DP_EINVAL, "dp_noise_assign: too few random words");
+  const int64_t total = (int64_t)pool + (int64_t)(cfg->block_num - 1) * nb;
+  *n_written = total;
+  if (capacity < total || !pool_index) return dp_set_error(DP_ENOMEM, "dp_noise_assign: capacity too small");
+  for (int32_t p = 0; p < pool; ++p) pool_index[p] = p;
+  const int32_t* tail = pool_index + pool - half;       // pool frames of the previous block's last num_c/2 frames
+  int32_t* blk = pool_index + pool;
+  int64_t w = 0;
+  for (int32_t b = 1; b < cfg->block_num; ++b, blk += nb) {
+    int32_t n = 0;
+    for (int32_t p = 0; p < pool; ++p) {
+      bool used = false;
+      for (int32_t t = 0; t < half; ++t) used = used || tail[t] == p;
+      if (!used) blk[n++] = p;
+    }
+    for (int32_t i = nb - 1; i >= 1; --i) {
+      const int32_t j = (int32_t)(random_words[w++] % (uint32_t)(i + 1));
+      const int32_t tmp = blk[i]; blk[i] = blk[j]; blk[j] = tmp;
+    }
+    tail = blk + nb - half;
+  }
+  return DP_OK;
+}

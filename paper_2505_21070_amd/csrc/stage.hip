@@ -22,6 +22,19 @@ int dp_set_error(int code, const char* msg) { return fail(code, "%s", msg); }
 
 static inline int64_t rup(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
 
+// ------------------------------------------------------------------------------------------ noise gather
+extern "C" int dp_noise_gather(const void* pool, int32_t pool_frames, int64_t frame_bytes, const int32_t* index,
+                               int32_t n_frames, void* out, void* hip_stream) {
+  if (pool_frames < 1 || n_frames < 0 || frame_bytes < 0) return fail(DP_EINVAL, "dp_noise_gather: negative size");
+  if (n_frames == 0 || frame_bytes == 0) return DP_OK;                  // nothing to copy
+  if (!pool || !index || !out) return fail(DP_EINVAL, "dp_noise_gather: null pointer");
+  if (frame_bytes % 16 || ((uintptr_t)pool & 15) || ((uintptr_t)out & 15))
+    return fail(DP_EINVAL, "dp_noise_gather: frames must be multiples of 16 bytes and 16-byte aligned");
+  if (n_frames > 65535) return fail(DP_EINVAL, "dp_noise_gather: more than 65535 frames in one call");
+  launch_gather_frames(pool, pool_frames, frame_bytes, index, n_frames, out, (hipStream_t)hip_stream);
+  return DP_OK;
+}
+
 // ------------------------------------------------------------------------------------------ layout
 struct LayerMem {
   float *gq, *gk, *cgq, *cgk, *ln3g, *ln3b;     // fp32 copies of the per-channel vectors

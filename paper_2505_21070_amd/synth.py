@@ -137,13 +137,13 @@ def to_numpy(weights):
             "layers": [{k: v.numpy() for k, v in lw.items()} for lw in weights["layers"]]}
 
 
-def noise_pool_blocks(cfg, block_num, pool_frames, gen):
-    """Token-space stand-in for a shared initial-noise pool: `pool_frames` N(0,1) frames; every block is a
-    seeded permutation of pool frames (so all blocks share one noise pattern)."""
+def shuffle_words(n, seed):
+    """n unsigned 32-bit random words (the random numbers the noise initialisation consumes), from one seed."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return [int(v) for v in torch.randint(0, 2**32, (n,), generator=g, dtype=torch.int64)]
+
+
+def noise_pool(cfg, pool_frames, gen):
+    """Token-space stand-in for the shared initial-noise pool: [pool_frames, tokens per frame, dim] N(0,1)."""
     tok = cfg["tok_h"] * cfg["tok_w"]
-    pool = round_to(torch.randn((pool_frames, tok, cfg["dim"]), generator=gen, dtype=torch.float32), cfg["dtype"])
-    blocks = []
-    for _ in range(block_num):
-        perm = torch.randperm(pool_frames, generator=gen)[: cfg["block_frames"]]
-        blocks.append(pool[perm].reshape(-1, cfg["dim"]).contiguous())
-    return blocks
+    return round_to(torch.randn((pool_frames, tok, cfg["dim"]), generator=gen, dtype=torch.float32), cfg["dtype"])

@@ -134,22 +134,31 @@ def test_stage_split_chains(name):
 
 def test_queue_sweep_matches_oracle():
     """Block queue of Sec. 3.1 on a tiny model: 4 blocks, T = 4, tail-to-head, each block reading the cache
-    of the block processed just before it; every pass compared with the oracle."""
+    of the block processed just before it, blocks initialised from the shared noise pool (Sec. 3.3: the
+    first block is the whole pool and Num_C/2 frames longer); every pass compared with the oracle."""
+    from oracle.noise import gather_frames, noise_assignment
     from paper_2505_21070_amd import binding as B
     cfg, w, text, _ = synth.make_case("tiny", seed=6, strong_gate=True)
     nb, T, num_b, num_c = 4, 4, cfg["block_frames"], 2 * cfg["cache_frames"]
+    pool_frames = num_b + num_c // 2
     gen = torch.Generator().manual_seed(7)
-    xs = synth.noise_pool_blocks(cfg, nb, num_b + num_c // 2, gen)
-    g = gpu_stage(cfg, w, text, max_abs_frames=nb * num_b)
+    pool = synth.noise_pool(cfg, pool_frames, gen)
+    words = synth.shuffle_words((nb - 1) * (num_b - 1), 8)
+    idx = B.noise_assign(nb, num_b, num_c, words)
+    assert idx == noise_assignment(nb, num_b, num_c, words)
+    pool_dev = pool.to("cuda")
+    xs_gpu = [B.noise_gather(pool_dev, torch.tensor(i, dtype=torch.int32, device="cuda")).reshape(-1, cfg["dim"]) for i in idx]
+    xs_ref = [gather_frames(pool.numpy(), i).reshape(-1, cfg["dim"]) for i in idx]
+    g = gpu_stage(cfg, w, text, max_block_frames=pool_frames, max_abs_frames=pool_frames + nb * num_b)
     o = oracle_stage(cfg, w, text)
-    sched = B.blockwise_schedule(T, nb, num_b, num_c, 0, 1000.0, "reverse")
+    sched = B.blockwise_schedule(T, nb, num_b, num_c, pool_frames, 1000.0, "reverse")
     assert len(sched) == T * nb
     for e in sched:
         if e["cache_block"] == 0:
             g.cache_update(0, 0); o.cache_update(0, 0)
-        x = xs[e["block"] - 1]
-        y = g.forward(to_dev(x, cfg), e["n_frames"], e["frame0"], e["timestep"])
-        r = o.forward(x.numpy(), e["n_frames"], e["frame0"], e["timestep"])
+        assert xs_gpu[e["block"] - 1].shape[0] == e["n_frames"] * cfg["tok_h"] * cfg["tok_w"]
+        y = g.forward(xs_gpu[e["block"] - 1], e["n_frames"], e["frame0"], e["timestep"])
+        r = o.forward(xs_ref[e["block"] - 1], e["n_frames"], e["frame0"], e["timestep"])
         check(f"queue/step{e['step']}/block{e['block']}", to_np(y), r, "f32")
         g.cache_update(0, num_c // 2); o.cache_update(0, num_c // 2)
 

@@ -111,10 +111,17 @@ def test_wan1p3b_full_queue_sweep_properties():
     cfg, w, text, _ = synth.make_case("wan1p3b_full", seed=2, strong_gate=False, n_blocks=0)
     nb, T, num_b, num_c = 3, 2, cfg["block_frames"], 2 * cfg["cache_frames"]
     gen = torch.Generator().manual_seed(5)
-    xs = [to_dev(b, cfg) for b in synth.noise_pool_blocks(cfg, nb, num_b + num_c // 2, gen)]
-    g = gpu_stage(cfg, w, text, max_abs_frames=nb * num_b)
-    fresh = gpu_stage(cfg, w, text, max_abs_frames=nb * num_b)
-    sched = B.blockwise_schedule(T, nb, num_b, num_c, 0, 1000.0, "reverse")
+    # blocks initialised from the shared noise pool (Sec. 3.3): block 1 is the whole pool, 2 frames longer
+    pool_frames = num_b + num_c // 2
+    pool = to_dev(synth.noise_pool(cfg, pool_frames, gen), cfg)
+    idx = B.noise_assign(nb, num_b, num_c, synth.shuffle_words((nb - 1) * (num_b - 1), 6))
+    xs = [B.noise_gather(pool, torch.tensor(i, dtype=torch.int32, device="cuda")).reshape(-1, cfg["dim"]) for i in idx]
+    for b in range(1, nb):
+        assert not set(idx[b - 1][-(num_c // 2):]) & set(idx[b]) and len(set(idx[b])) == num_b
+    kw = dict(max_block_frames=pool_frames, max_abs_frames=pool_frames + nb * num_b)
+    g = gpu_stage(cfg, w, text, **kw)
+    fresh = gpu_stage(cfg, w, text, **kw)
+    sched = B.blockwise_schedule(T, nb, num_b, num_c, pool_frames, 1000.0, "reverse")
     assert len(sched) == T * nb
     for e in sched:
         x = xs[e["block"] - 1]

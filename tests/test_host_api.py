@@ -77,3 +77,25 @@ def test_config_validation_without_gpu(B):
     assert B._lib.dp_stage_forward(None, None, None, 1, 0, 0.0, None) == B.DP_EINVAL
     assert B._lib.dp_cache_update(None, 0, 1, None) == B.DP_EINVAL
     B._lib.dp_stage_free(None)
+
+
+@pytest.mark.parametrize("block_num,num_b,num_c", [(8, 4, 4), (5, 4, 2), (6, 8, 8), (7, 3, 6), (4, 5, 0), (4, 1, 2), (1, 4, 4)])
+@pytest.mark.parametrize("seed", [0, 3])
+def test_noise_assignment_matches_oracle(B, block_num, num_b, num_c, seed):
+    from oracle.noise import noise_assignment
+    from paper_2505_21070_amd import synth
+    words = synth.shuffle_words((block_num - 1) * (num_b - 1) + 2, seed)
+    assert B.noise_assign(block_num, num_b, num_c, words) == noise_assignment(block_num, num_b, num_c, words)
+
+
+def test_noise_assignment_bad_input(B):
+    import ctypes as C
+    cfg = B.NoiseConfig(3, 4, 4)
+    n = C.c_int64()
+    words = (C.c_uint32 * 6)(*range(6))
+    assert B._lib.dp_noise_assign(C.byref(cfg), words, 6, None, 0, C.byref(n)) == B.DP_ENOMEM and n.value == 6 + 2 * 4
+    assert B._lib.dp_noise_assign(C.byref(cfg), words, 5, None, 0, C.byref(n)) == B.DP_EINVAL      # too few words
+    assert B._lib.dp_noise_assign(None, words, 6, None, 0, C.byref(n)) == B.DP_EINVAL
+    bad = B.NoiseConfig(0, 4, 4)
+    assert B._lib.dp_noise_assign(C.byref(bad), words, 6, None, 0, C.byref(n)) == B.DP_EINVAL
+    assert b"dp_noise_assign" in B._lib.dp_last_error()
