@@ -122,6 +122,13 @@ int dp_cache_update(dp_stage_t* stage, int32_t first_frame, int32_t n_frames, vo
 
 /* Queue schedule of block-wise denoising (Sec. 3.1, 3.2, 3.3). */
 enum { DP_ORDER_REVERSE = 0 /* tail to head, the paper's choice */, DP_ORDER_SEQUENTIAL = 1 /* head to tail */ };
+/* What a pass feeds the model (Sec. 3.2).  A neighbour counts only while it is in the queue itself.
+ *   DP_INPUT_BLOCK    : the block alone; the neighbour processed just before it is present through the cache
+ *   DP_INPUT_EXTENDED : the paper's B_i' = [B_{i-1}, B_i] with the feature cache standing in for B_{i+1}:
+ *                       the num_c/2 touching frames of the neighbour processed AFTER this block are fed
+ *                       along with it
+ *   DP_INPUT_NOCACHE  : B_i' = [B_{i-1}, B_i, B_{i+1}] fed whole, nothing cached (the ablation's baseline) */
+enum { DP_INPUT_BLOCK = 0, DP_INPUT_EXTENDED = 1, DP_INPUT_NOCACHE = 2 };
 
 typedef struct {
   int32_t T;                  /* denoising steps = number of noise levels                         */
@@ -131,6 +138,7 @@ typedef struct {
   int32_t first_block_frames; /* frames of block 1 (Sec. 3.3: num_b + num_c/2); 0 means num_b     */
   int32_t order;              /* DP_ORDER_*                                                       */
   float t_max;                /* timestep of level T; level k maps to t_max * k / T               */
+  int32_t input;              /* DP_INPUT_*                                                       */
 } dp_sched_config;
 
 typedef struct {
@@ -140,7 +148,11 @@ typedef struct {
   float timestep;
   int32_t frame0, n_frames;   /* absolute first frame and length of the block                     */
   int32_t cache_block;        /* block whose K/V this pass attends to (processed just before); 0 = none */
-  int32_t cache_first, cache_frames; /* retained frames of cache_block, relative to its first frame */
+  int32_t cache_first, cache_frames; /* retained frames of cache_block's pass, relative to the first frame
+                                        that pass fed (its in_frame0): the arguments of dp_cache_update   */
+  int32_t in_frame0, in_frames; /* the frames to feed dp_stage_forward (= frame0, n_frames for DP_INPUT_BLOCK) */
+  int32_t keep_first;         /* offset of the block's own n_frames frames inside the fed frames; the
+                                 other output rows are discarded                                     */
 } dp_sched_entry;
 
 /*

@@ -44,13 +44,14 @@ class StageWeights(C.Structure):
 
 class SchedConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("T", "block_num", "num_b", "num_c", "first_block_frames", "order")] + \
-               [("t_max", C.c_float)]
+               [("t_max", C.c_float), ("input", C.c_int32)]
 
 
 class SchedEntry(C.Structure):
     _fields_ = [("step", C.c_int32), ("block", C.c_int32), ("level", C.c_int32), ("timestep", C.c_float),
                 ("frame0", C.c_int32), ("n_frames", C.c_int32), ("cache_block", C.c_int32),
-                ("cache_first", C.c_int32), ("cache_frames", C.c_int32)]
+                ("cache_first", C.c_int32), ("cache_frames", C.c_int32), ("in_frame0", C.c_int32),
+                ("in_frames", C.c_int32), ("keep_first", C.c_int32)]
 
 
 _lib.dp_stage_workspace_bytes.restype = C.c_size_t
@@ -221,8 +222,11 @@ class Stage:
             pass
 
 
-def blockwise_schedule(T, block_num, num_b, num_c, first_block_frames=0, t_max=1000.0, order="reverse"):
-    cfg = SchedConfig(T, block_num, num_b, num_c, first_block_frames, ORDER[order], t_max)
+INPUT = {"block": 0, "extended": 1, "nocache": 2}
+
+
+def blockwise_schedule(T, block_num, num_b, num_c, first_block_frames=0, t_max=1000.0, order="reverse", variant="block"):
+    cfg = SchedConfig(T, block_num, num_b, num_c, first_block_frames, ORDER[order], t_max, INPUT[variant])
     n = C.c_int64()
     rc = _lib.dp_blockwise_schedule(C.byref(cfg), None, 0, C.byref(n))
     if rc not in (DP_OK, DP_ENOMEM):

@@ -15,6 +15,8 @@ extern "C" int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry*
     return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: non-positive size");
   if (cfg->order != DP_ORDER_REVERSE && cfg->order != DP_ORDER_SEQUENTIAL)
     return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: unknown order");
+  if (cfg->input != DP_INPUT_BLOCK && cfg->input != DP_INPUT_EXTENDED && cfg->input != DP_INPUT_NOCACHE)
+    return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: unknown input variant");
   const int64_t total = (int64_t)cfg->T * cfg->block_num;
   *n_written = total;
   if (capacity < total || !out) return dp_set_error(DP_ENOMEM, "dp_blockwise_schedule: capacity too small");
@@ -22,27 +24,34 @@ extern "C" int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry*
   const int32_t first = cfg->first_block_frames > 0 ? cfg->first_block_frames : cfg->num_b;
   auto frames_of = [&](int32_t b) { return b == 1 ? first : cfg->num_b; };
   auto start_of = [&](int32_t b) { return b == 1 ? 0 : first + (b - 2) * cfg->num_b; };
+  auto ctx_of = [&](int32_t b) { const int32_t f = frames_of(b); return half < f ? half : f; };  // frames a neighbour sees
   int64_t n = 0;
   for (int32_t step = 1; step <= T + B - 1; ++step) {
     int32_t lo = step - T + 1; if (lo < 1) lo = 1;        // cleanest block still queued (head)
     int32_t hi = step < B ? step : B;                     // newest block (tail)
     const bool rev = cfg->order == DP_ORDER_REVERSE;
-    int32_t prev = 0;
+    int32_t prev = 0, prev_keep = 0;
     for (int32_t i = 0; i <= hi - lo; ++i) {
       const int32_t b = rev ? hi - i : lo + i;
       dp_sched_entry e;
       e.step = step; e.block = b; e.level = T - (step - b);
       e.timestep = cfg->t_max * (float)e.level / (float)T;
       e.frame0 = start_of(b); e.n_frames = frames_of(b);
+      // Sec. 3.2: frames of the queued neighbours fed along with the block
+      const int32_t before = b - 1 >= lo ? ctx_of(b - 1) : 0, after = b + 1 <= hi ? ctx_of(b + 1) : 0;
+      int32_t lead = 0, trail = 0;
+      if (cfg->input == DP_INPUT_EXTENDED) { if (rev) lead = before; else trail = after; }
+      else if (cfg->input == DP_INPUT_NOCACHE) { lead = before; trail = after; }
+      e.in_frame0 = e.frame0 - lead; e.in_frames = lead + e.n_frames + trail; e.keep_first = lead;
       e.cache_block = 0; e.cache_first = 0; e.cache_frames = 0;
-      if (prev != 0 && half > 0) {
-        const int32_t pf = frames_of(prev);
+      if (prev != 0 && half > 0 && cfg->input != DP_INPUT_NOCACHE) {
         e.cache_block = prev;
-        e.cache_frames = half < pf ? half : pf;
-        e.cache_first = rev ? 0 : pf - e.cache_frames;    // the neighbour's frames that touch block b
+        e.cache_frames = ctx_of(prev);
+        // the neighbour's frames that touch block b, counted from the first frame its pass fed
+        e.cache_first = prev_keep + (rev ? 0 : frames_of(prev) - e.cache_frames);
       }
       out[n++] = e;
-      prev = b;
+      prev = b; prev_keep = lead;
     }
   }
   return DP_OK;

@@ -163,6 +163,45 @@ def test_queue_sweep_matches_oracle():
         g.cache_update(0, num_c // 2); o.cache_update(0, num_c // 2)
 
 
+@pytest.mark.parametrize("variant", ["extended", "nocache"])
+def test_extended_block_queue_matches_oracle(variant):
+    """Sec. 3.2 on a tiny model: every pass feeds the frames the library's schedule names (the block plus the
+    touching frames of its queued neighbours), keeps what the schedule says to cache, and is compared with the
+    oracle driven by the oracle's own schedule."""
+    from oracle.schedule import blockwise_schedule as oracle_schedule
+    from paper_2505_21070_amd import binding as B
+    cfg, w, text, _ = synth.make_case("tiny", seed=9, strong_gate=True)
+    nb, T, num_b, num_c = 4, 3, cfg["block_frames"], 2 * cfg["cache_frames"]
+    first = num_b + num_c // 2
+    tok = cfg["tok_h"] * cfg["tok_w"]
+    total = first + (nb - 1) * num_b
+    gen = torch.Generator().manual_seed(10)
+    video = synth.round_to(torch.randn((total * tok, cfg["dim"]), generator=gen, dtype=torch.float32), cfg["dtype"])
+    sched = B.blockwise_schedule(T, nb, num_b, num_c, first, 1000.0, "reverse", variant)
+    ref_sched = oracle_schedule(T, nb, num_b, num_c, first, 1000.0, "reverse", variant)
+    longest = max(e["in_frames"] for e in sched)
+    assert longest == (first if variant == "extended" else first + num_c // 2)
+    g = gpu_stage(cfg, w, text, max_block_frames=longest, max_abs_frames=total)
+    o = oracle_stage(cfg, w, text)
+    video_dev = to_dev(video, cfg)
+    for i, (e, r) in enumerate(zip(sched, ref_sched)):
+        if e["cache_block"] == 0:
+            g.cache_update(0, 0)
+        if r["cache_block"] == 0:
+            o.cache_update(0, 0)
+        rows = slice(e["in_frame0"] * tok, (e["in_frame0"] + e["in_frames"]) * tok)
+        rrows = slice(r["in_frame0"] * tok, (r["in_frame0"] + r["in_frames"]) * tok)
+        y = g.forward(video_dev[rows].contiguous(), e["in_frames"], e["in_frame0"], e["timestep"])
+        ref = o.forward(video[rrows].numpy(), r["in_frames"], r["in_frame0"], r["timestep"])
+        keep = slice(e["keep_first"] * tok, (e["keep_first"] + e["n_frames"]) * tok)      # the block's own rows
+        check(f"{variant}/step{e['step']}/block{e['block']}", to_np(y)[keep], ref[keep], "f32")
+        check(f"{variant}/step{e['step']}/block{e['block']}/all", to_np(y), ref, "f32")
+        if i + 1 < len(sched) and sched[i + 1]["cache_block"] == e["block"]:
+            g.cache_update(sched[i + 1]["cache_first"], sched[i + 1]["cache_frames"])
+        if i + 1 < len(ref_sched) and ref_sched[i + 1]["cache_block"] == r["block"]:
+            o.cache_update(ref_sched[i + 1]["cache_first"], ref_sched[i + 1]["cache_frames"])
+
+
 def test_error_paths_leave_gpu_alone():
     from paper_2505_21070_amd import binding as B
     cfg, w, text, blocks = synth.make_case("tiny", seed=0)

@@ -33,9 +33,10 @@ def test_exports_every_declared_symbol(B):
 
 @pytest.mark.parametrize("args", [(8, 8, 4, 4, 0), (50, 4, 8, 8, 0), (4, 3, 4, 2, 5), (3, 1, 4, 4, 0), (5, 7, 4, 0, 0)])
 @pytest.mark.parametrize("order", ["reverse", "sequential"])
-def test_schedule_matches_oracle(B, args, order):
-    got = B.blockwise_schedule(*args, 1000.0, order)
-    ref = oracle_schedule(args[0], args[1], args[2], args[3], args[4] or None, 1000.0, order)
+@pytest.mark.parametrize("variant", ["block", "extended", "nocache"])
+def test_schedule_matches_oracle(B, args, order, variant):
+    got = B.blockwise_schedule(*args, 1000.0, order, variant)
+    ref = oracle_schedule(args[0], args[1], args[2], args[3], args[4] or None, 1000.0, order, variant)
     assert len(got) == len(ref) == args[0] * args[1]
     for g, r in zip(got, ref):
         for k, v in r.items():
@@ -49,6 +50,8 @@ def test_schedule_capacity_and_bad_input(B):
     assert B._lib.dp_blockwise_schedule(C.byref(cfg), arr, 5, C.byref(n)) == B.DP_ENOMEM and n.value == 12
     assert "capacity" in B.last_error()
     bad = B.SchedConfig(0, 3, 4, 4, 0, 0, 1000.0)
+    assert B._lib.dp_blockwise_schedule(C.byref(bad), arr, 5, C.byref(n)) == B.DP_EINVAL
+    bad = B.SchedConfig(4, 3, 4, 4, 0, 0, 1000.0, 3)                       # unknown input variant
     assert B._lib.dp_blockwise_schedule(C.byref(bad), arr, 5, C.byref(n)) == B.DP_EINVAL
     assert B._lib.dp_blockwise_schedule(None, arr, 5, C.byref(n)) == B.DP_EINVAL
 

@@ -98,3 +98,59 @@ def test_longer_first_block_and_sequential_order():
     long = blockwise_schedule(2, 64, num_b=4, num_c=4, first_block_frames=5)
     last = max(long, key=lambda e: e["frame0"])
     assert last["frame0"] + last["n_frames"] == 257
+
+
+def _abs_frames(first, n):
+    return set(range(first, first + n))
+
+
+@pytest.mark.parametrize("order", ["reverse", "sequential"])
+@pytest.mark.parametrize("T,block_num,num_b,num_c,first", [(4, 5, 4, 4, 6), (3, 4, 8, 8, None), (6, 3, 2, 4, 4), (2, 6, 3, 2, None)])
+def test_extended_block_and_feature_cache(T, block_num, num_b, num_c, first, order):
+    """Sec. 3.2: with the feature cache the input shrinks from [B_{i-1}, B_i, B_{i+1}] to [B_{i-1}, B_i] and the
+    cached K/V are exactly the frames that were dropped."""
+    blk = blockwise_schedule(T, block_num, num_b, num_c, first, order=order)
+    ext = blockwise_schedule(T, block_num, num_b, num_c, first, order=order, variant="extended")
+    noc = blockwise_schedule(T, block_num, num_b, num_c, first, order=order, variant="nocache")
+    assert len(blk) == len(ext) == len(noc) == T * block_num
+    half = num_c // 2
+    total = (first or num_b) + (block_num - 1) * num_b
+    by_key = {(e["step"], e["block"]): e for e in ext}
+    for b0, e, n in zip(blk, ext, noc):
+        for k in ("step", "block", "level", "timestep", "frame0", "n_frames"):
+            assert b0[k] == e[k] == n[k]
+        assert (b0["in_frame0"], b0["in_frames"], b0["keep_first"]) == (b0["frame0"], b0["n_frames"], 0)
+        for x in (e, n):
+            own = _abs_frames(x["in_frame0"] + x["keep_first"], x["n_frames"])
+            assert own == _abs_frames(x["frame0"], x["n_frames"])              # the block sits at keep_first
+            assert 0 <= x["in_frame0"] and x["in_frame0"] + x["in_frames"] <= total
+        assert n["cache_block"] == 0 and n["in_frames"] <= n["n_frames"] + num_c
+        assert e["in_frames"] <= e["n_frames"] + half                          # the reduced input of Sec. 3.2
+        cached = set()
+        if e["cache_block"]:
+            src = by_key[(e["step"], e["cache_block"])]
+            assert src["block"] == e["block"] + (1 if order == "reverse" else -1)
+            assert 0 <= e["cache_first"] and e["cache_first"] + e["cache_frames"] <= src["in_frames"]
+            cached = _abs_frames(src["in_frame0"] + e["cache_first"], e["cache_frames"])
+            assert cached <= _abs_frames(src["frame0"], src["n_frames"])      # the neighbour's own frames
+            assert b0["cache_frames"] == e["cache_frames"]
+        # fed frames + cached frames = what is fed without the cache
+        assert _abs_frames(e["in_frame0"], e["in_frames"]) | cached == _abs_frames(n["in_frame0"], n["in_frames"])
+        assert not _abs_frames(e["in_frame0"], e["in_frames"]) & cached
+
+
+def test_extended_block_example_by_hand():
+    # T = 2, 3 blocks of 4 frames, Num_C = 4, tail to head.  Step 2 holds blocks 2 and 1 (block 3 is not there
+    # yet): block 2 is fed [frames 2,3 of block 1 ; block 2] = frames 2..7, no cache; block 1 is fed alone
+    # (it has no earlier neighbour) and reads the K/V of block 2's first two frames, which sit at offset 2 of
+    # that pass's input.  Without the cache block 1 is fed frames 0..5.
+    ext = [e for e in blockwise_schedule(2, 3, 4, 4, variant="extended") if e["step"] == 2]
+    assert [(e["block"], e["in_frame0"], e["in_frames"], e["keep_first"], e["cache_block"], e["cache_first"], e["cache_frames"])
+            for e in ext] == [(2, 2, 6, 2, 0, 0, 0), (1, 0, 4, 0, 2, 2, 2)]
+    noc = [e for e in blockwise_schedule(2, 3, 4, 4, variant="nocache") if e["step"] == 2]
+    assert [(e["block"], e["in_frame0"], e["in_frames"], e["keep_first"]) for e in noc] == [(2, 2, 6, 2), (1, 0, 6, 0)]
+    # step 3: blocks 3 and 2 (block 1 has left the queue and no longer counts as a neighbour); block 3 is fed
+    # [frames 6,7 ; block 3], block 2 is fed alone and reads block 3's first two frames at offset 2
+    ext3 = [e for e in blockwise_schedule(2, 3, 4, 4, variant="extended") if e["step"] == 3]
+    assert [(e["block"], e["in_frame0"], e["in_frames"], e["keep_first"], e["cache_block"], e["cache_first"], e["cache_frames"])
+            for e in ext3] == [(3, 6, 6, 2, 0, 0, 0), (2, 4, 4, 0, 3, 2, 2)]
