@@ -115,8 +115,11 @@ int dp_stage_forward(dp_stage_t* stage, const void* x_in, void* x_out, int32_t n
  * values of frames [first_frame, first_frame + n_frames) of the block the last dp_stage_forward
  * processed (frame indices relative to that block).  The cached keys carry their absolute
  * positions, so the next block may lie before or after them.  n_frames == 0 empties the cache.
+ * No data moves and nothing is launched: the frames stay where the forward wrote them, and the next
+ * forward writes its own keys and values directly before or after them in the per-layer buffer (which
+ * has room for two blocks plus the cache).  hip_stream is accepted for symmetry and not used.
  * Errors: DP_ESTATE (no forward yet), DP_EINVAL (range outside the last block or above
- * max_cache_frames), DP_EHIP.
+ * max_cache_frames).
  */
 int dp_cache_update(dp_stage_t* stage, int32_t first_frame, int32_t n_frames, void* hip_stream);
 

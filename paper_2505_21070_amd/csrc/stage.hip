@@ -38,7 +38,7 @@ extern "C" int dp_noise_gather(const void* pool, int32_t pool_frames, int64_t fr
 // ------------------------------------------------------------------------------------------ layout
 struct LayerMem {
   float *gq, *gk, *cgq, *cgk, *ln3g, *ln3b;     // fp32 copies of the per-channel vectors
-  void *kbuf, *vtbuf;                           // [h][Lpad][d], [h][d][Lpad]: cache right-aligned at Ncmax, block after it
+  void *kbuf, *vtbuf;                           // [h][Lpad][d], [h][d][Lpad]: rows / columns = key positions of the buffer
   void *tk, *tvt;                               // text keys [h][Ltpad][d], text values transposed [h][d][Ltpad]
   void *wqkv_t, *bqkv, *wo_t, *cwq_t, *cwo_t, *w1_t, *w2_t;   // bf16 path: weights as [out(pad 256), in]
 };
@@ -79,7 +79,11 @@ struct dp_stage {
   void* tap_attn; float *tap_xself, *tap_xcross;
   float* attn_scratch;
   // state
-  int64_t cache_len = 0, last_S = 0; int last_frames = 0;
+  // Key buffer geometry (rows of kbuf = columns of vtbuf, the same in every layer).  The last block's keys
+  // sit at [blk0, blk0 + last_S); the feature cache is the sub-range [cache0, cache0 + cache_len) of it that
+  // dp_cache_update named.  The next block is written directly before or directly after the cache, so the
+  // keys an attention call reads are always one contiguous range and retaining frames moves no data.
+  int64_t blk0 = 0, cache0 = 0, cache_len = 0, last_S = 0; int last_frames = 0;
 };
 
 struct Carver {
@@ -126,7 +130,7 @@ static size_t carve(dp_stage* s, void* base) {
   s->Smax = s->tok * c.max_block_frames;
   s->Ncmax = s->tok * c.max_cache_frames;
   s->Spad = rup(s->Smax, 256);
-  s->Lpad = rup(s->Ncmax + s->Smax, 64) + 64;
+  s->Lpad = rup(2 * s->Smax + s->Ncmax, 64) + 64;     // a block fits on one side of any cached range
   s->Ltpad = rup(c.text_len, 256);
   const int64_t D = c.dim, F = c.ffn_dim, E = s->esz, L = c.n_layers;
   Carver cv(base);
@@ -335,6 +339,14 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
        launch_gemv<T>(s->e2, (int)D, (const T*)s->w.wm, (const T*)s->w.bm, (int)(6 * D), 1, s->e0, st);
        launch_mod_add(s->mtab, s->e0, s->mod, c.n_layers, (int)(6 * D), st));
   const int64_t kv_hs = s->Lpad * d;        // head stride of kbuf
+  // where this block's keys go: directly before the cached range if it fits there, else directly after it
+  // (the buffer holds 2 * Smax + Ncmax positions, so one side always has room)
+  int64_t blk0 = 0, key0 = 0;
+  if (s->cache_len > 0) {
+    if (s->cache0 >= S) { blk0 = s->cache0 - S; key0 = blk0; }
+    else { blk0 = s->cache0 + s->cache_len; key0 = s->cache0; }
+  }
+  s->blk0 = blk0;
   for (int l = 0; l < c.n_layers; ++l) {
     const dp_layer_weights& w = s->lw[(size_t)l]; LayerMem& m = s->lm[(size_t)l];
     const float* md = s->mod + (int64_t)l * 6 * D;
@@ -352,11 +364,11 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
     }
     PROF(DP_PROF_NORM_ROPE,
          const NormRopeJob<T> qk[2] = {{0, m.gq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, 1},
-                                       {(int)D, m.gk, 1.f, (T*)m.kbuf, kv_hs, s->Ncmax, 1}};
+                                       {(int)D, m.gk, 1.f, (T*)m.kbuf, kv_hs, blk0, 1}};
          launch_norm_rope<T>((const T*)s->raw, 3 * D, S, h, d, c.eps, qk, 2, &s->rt, frame0, c.tok_h, c.tok_w, st);
-         launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, s->Ncmax, st));
+         launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, blk0, st));
     PROF(DP_PROF_SELF_ATTN,
-         Path<T>::attn(s->qbuf, s->Spad * d, m.kbuf, kv_hs, s->Ncmax - s->cache_len, m.vtbuf, s->Lpad, S,
+         Path<T>::attn(s->qbuf, s->Spad * d, m.kbuf, kv_hs, key0, m.vtbuf, s->Lpad, S,
                        s->cache_len + S, h, d, s->attn_o, D, s->attn_scratch, st));
     if (s->tap_attn && l == c.n_layers - 1) launch_copy2d<T>((const T*)s->attn_o, 0, (T*)s->tap_attn, 0, 1, S * D, st);
     PROF(DP_PROF_OPROJ_GEMM, Path<T>::gemm(s->attn_o, D, w.wo, m.wo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.bo, g1), st));
@@ -398,18 +410,6 @@ extern "C" int dp_stage_forward(dp_stage_t* s, const void* x_in, void* x_out, in
 }
 
 // ------------------------------------------------------------------------------------------ cache
-template <typename T>
-static void cache_typed(dp_stage* s, int first, int n, hipStream_t st) {
-  const int h = s->cfg.n_heads, d = s->cfg.head_dim;
-  const int64_t len = s->tok * n, src0 = s->Ncmax + s->tok * first, dst0 = s->Ncmax - len;
-  for (size_t l = 0; l < s->lm.size(); ++l) {
-    T* kb = (T*)s->lm[l].kbuf; T* vb = (T*)s->lm[l].vtbuf;
-    PROF(DP_PROF_CACHE_COPY,
-         launch_copy2d<T>(kb + src0 * d, s->Lpad * d, kb + dst0 * d, s->Lpad * d, h, len * d, st);
-         launch_copy2d<T>(vb + src0, s->Lpad, vb + dst0, s->Lpad, (int64_t)h * d, len, st));
-  }
-}
-
 extern "C" int dp_cache_update(dp_stage_t* s, int32_t first_frame, int32_t n_frames, void* hip_stream) {
   if (!s) return fail(DP_EINVAL, "dp_cache_update: null stage");
   if (n_frames == 0) { s->cache_len = 0; return DP_OK; }
@@ -419,12 +419,9 @@ extern "C" int dp_cache_update(dp_stage_t* s, int32_t first_frame, int32_t n_fra
   if (first_frame < 0 || first_frame + n_frames > s->last_frames)
     return fail(DP_EINVAL, "dp_cache_update: frames [%d, %d) outside the last block's %d frames", first_frame,
                 first_frame + n_frames, s->last_frames);
-  hipStream_t st = (hipStream_t)hip_stream;
-  (void)hipGetLastError();
-  if (s->cfg.dtype == DP_BF16) cache_typed<bf16_t>(s, first_frame, n_frames, st);
-  else cache_typed<float>(s, first_frame, n_frames, st);
-  const hipError_t err = hipGetLastError();
-  if (err != hipSuccess) return fail(DP_EHIP, "dp_cache_update: %s", hipGetErrorString(err));
+  // nothing is copied: the frames stay where the last forward wrote them and the next block goes around them
+  (void)hip_stream;
+  s->cache0 = s->blk0 + s->tok * first_frame;
   s->cache_len = s->tok * n_frames;
   return DP_OK;
 }
@@ -447,10 +444,10 @@ static int peek_typed(dp_stage* s, int what, int layer, float* dst, int64_t cap,
   if (cap < n * D) return fail(DP_ENOMEM, "dp_stage_peek: need %lld floats", (long long)(n * D));
   if (n == 0) return DP_OK;
   switch (what) {
-    case DP_PEEK_K: launch_gather_heads<T>((const T*)m.kbuf, s->Lpad * d, s->Ncmax, n, h, d, dst, st); break;
-    case DP_PEEK_V: launch_gather_vt<T>((const T*)m.vtbuf, s->Lpad, s->Ncmax, n, h, d, dst, st); break;
-    case DP_PEEK_CACHE_K: launch_gather_heads<T>((const T*)m.kbuf, s->Lpad * d, s->Ncmax - n, n, h, d, dst, st); break;
-    case DP_PEEK_CACHE_V: launch_gather_vt<T>((const T*)m.vtbuf, s->Lpad, s->Ncmax - n, n, h, d, dst, st); break;
+    case DP_PEEK_K: launch_gather_heads<T>((const T*)m.kbuf, s->Lpad * d, s->blk0, n, h, d, dst, st); break;
+    case DP_PEEK_V: launch_gather_vt<T>((const T*)m.vtbuf, s->Lpad, s->blk0, n, h, d, dst, st); break;
+    case DP_PEEK_CACHE_K: launch_gather_heads<T>((const T*)m.kbuf, s->Lpad * d, s->cache0, n, h, d, dst, st); break;
+    case DP_PEEK_CACHE_V: launch_gather_vt<T>((const T*)m.vtbuf, s->Lpad, s->cache0, n, h, d, dst, st); break;
     case DP_PEEK_TEXT_K: launch_gather_heads<T>((const T*)m.tk, s->Ltpad * d, 0, n, h, d, dst, st); break;
     case DP_PEEK_TEXT_V: launch_gather_vt<T>((const T*)m.tvt, s->Ltpad, 0, n, h, d, dst, st); break;
     case DP_PEEK_Q: launch_gather_heads<T>((const T*)s->qbuf, s->Spad * d, 0, n, h, d, dst, st); break;
