@@ -173,6 +173,18 @@ int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry* out, int64
  * (N <= block_num / N > block_num), Eq. 5 for DP_ORDER_SEQUENTIAL.  Host only.  Returns -1 on bad input. */
 double dp_bubble_ratio(int32_t n_devices, int32_t T, int32_t block_num, int32_t order);
 
+/* Slot-level count of the device pipeline that runs the block queue (Sec. 3.1, 3.4, appendix on the denoising
+ * order): the model is split over n_devices devices; a block pass occupies devices 1..N for one slot each, in
+ * order; a device takes the passes in the queue schedule's order, one at a time; a block's pass of the next
+ * diffusion step enters device 1 only after its pass of this step has left device N.  Host only.
+ *   makespan          : out, slots until the last pass leaves the last device
+ *   bubble_per_device : out, makespan - T * block_num, the idle slots of each device
+ * For T > N and block_num >= 2 the count equals the numerators of Eq. 5 and Eq. 4, and (N-1)^2 for the
+ * tail-to-head order with N <= block_num (Eq. 3 prints N^2-N-1; dp_bubble_ratio returns the printed forms).
+ * Errors: DP_EINVAL (null pointer, non-positive size, unknown order). */
+int dp_pipeline_simulate(int32_t n_devices, int32_t T, int32_t block_num, int32_t order, int64_t* makespan,
+                         int64_t* bubble_per_device);
+
 /*
  * Coordinated noise initialisation (Sec. 3.3, overview figure): every block's initial noise is taken
  * from one shared pool of num_b + num_c/2 frame noises.  Block 1 is the whole pool in its stored order

@@ -85,6 +85,8 @@ _lib.dp_noise_assign.argtypes = [C.POINTER(NoiseConfig), C.POINTER(C.c_uint32), 
                                  C.c_int64, C.POINTER(C.c_int64)]
 _lib.dp_noise_gather.restype = C.c_int
 _lib.dp_noise_gather.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+_lib.dp_pipeline_simulate.restype = C.c_int
+_lib.dp_pipeline_simulate.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
 _lib.dp_probe_mfma_bf16.restype = C.c_int
 _lib.dp_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_double)]
 _lib.dp_stage_free.argtypes = [C.c_void_p]
@@ -238,6 +240,13 @@ def blockwise_schedule(T, block_num, num_b, num_c, first_block_frames=0, t_max=1
 
 def bubble_ratio(n_devices, T, block_num, order="reverse"):
     return float(_lib.dp_bubble_ratio(n_devices, T, block_num, ORDER[order]))
+
+
+def pipeline_simulate(n_devices, T, block_num, order="reverse"):
+    """(makespan, idle slots per device) of the N-device pipeline running the block queue."""
+    mk, bub = C.c_int64(), C.c_int64()
+    _check(_lib.dp_pipeline_simulate(n_devices, T, block_num, ORDER[order], C.byref(mk), C.byref(bub)), "dp_pipeline_simulate")
+    return mk.value, bub.value
 
 
 def noise_assign(block_num, num_b, num_c, words):

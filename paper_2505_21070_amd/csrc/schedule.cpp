@@ -1,4 +1,6 @@
 // Host-side queue schedule of block-wise denoising and the paper's bubble-ratio closed forms.
+#include <vector>
+
 #include "../../include/dualparal.h"
 
 int dp_set_error(int code, const char* msg);   // defined next to dp_last_error
@@ -66,6 +68,34 @@ extern "C" double dp_bubble_ratio(int32_t N, int32_t T, int32_t block_num, int32
   else if (N <= block_num) bubble = (double)N * N - N - 1.0;
   else bubble = (double)block_num * (N - T) + (double)N * (T - 2) + 1.0;
   return bubble / (bubble + (double)T * block_num);
+}
+
+// Sec. 3.4 / appendix: in-order pipeline of N one-slot stages fed by the queue schedule; a block's next pass waits
+// for its previous pass to leave the last stage.
+extern "C" int dp_pipeline_simulate(int32_t N, int32_t T, int32_t block_num, int32_t order, int64_t* makespan,
+                                    int64_t* bubble_per_device) {
+  if (!makespan || !bubble_per_device) return dp_set_error(DP_EINVAL, "dp_pipeline_simulate: null pointer");
+  if (N < 1 || T < 1 || block_num < 1) return dp_set_error(DP_EINVAL, "dp_pipeline_simulate: non-positive size");
+  if (order != DP_ORDER_REVERSE && order != DP_ORDER_SEQUENTIAL)
+    return dp_set_error(DP_EINVAL, "dp_pipeline_simulate: unknown order");
+  std::vector<int64_t> free_at((size_t)N, 0), done((size_t)block_num + 1, 0);
+  for (int32_t step = 1; step <= T + block_num - 1; ++step) {
+    int32_t lo = step - T + 1; if (lo < 1) lo = 1;
+    const int32_t hi = step < block_num ? step : block_num;
+    for (int32_t i = 0; i <= hi - lo; ++i) {
+      const int32_t b = order == DP_ORDER_REVERSE ? hi - i : lo + i;
+      int64_t t = done[(size_t)b];
+      for (int32_t j = 0; j < N; ++j) {
+        const int64_t start = t > free_at[(size_t)j] ? t : free_at[(size_t)j];
+        free_at[(size_t)j] = start + 1;
+        t = start + 1;
+      }
+      done[(size_t)b] = t;
+    }
+  }
+  *makespan = free_at[(size_t)N - 1];
+  *bubble_per_device = *makespan - (int64_t)T * block_num;
+  return DP_OK;
 }
 
 // Sec. 3.3: block 1 is the whole pool; a later block is a shuffle of the pool frames that the last

@@ -102,3 +102,16 @@ def test_noise_assignment_bad_input(B):
     bad = B.NoiseConfig(0, 4, 4)
     assert B._lib.dp_noise_assign(C.byref(bad), words, 6, None, 0, C.byref(n)) == B.DP_EINVAL
     assert b"dp_noise_assign" in B._lib.dp_last_error()
+
+
+def test_pipeline_simulation_matches_oracle(B):
+    import ctypes as C
+    from oracle.pipeline import simulate_pipeline
+    for order in ("reverse", "sequential"):
+        for N, T, Bn in [(1, 3, 2), (2, 2, 2), (4, 50, 4), (4, 50, 3), (4, 50, 8), (8, 50, 64), (5, 3, 7), (3, 9, 1)]:
+            r = simulate_pipeline(N, T, Bn, order)
+            assert B.pipeline_simulate(N, T, Bn, order) == (r["makespan"], r["bubble_per_device"])
+    mk, bub = C.c_int64(), C.c_int64()
+    assert B._lib.dp_pipeline_simulate(0, 5, 5, 0, C.byref(mk), C.byref(bub)) == B.DP_EINVAL
+    assert B._lib.dp_pipeline_simulate(2, 5, 5, 7, C.byref(mk), C.byref(bub)) == B.DP_EINVAL
+    assert B._lib.dp_pipeline_simulate(2, 5, 5, 0, None, C.byref(bub)) == B.DP_EINVAL
