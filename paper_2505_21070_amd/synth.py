@@ -147,3 +147,18 @@ def noise_pool(cfg, pool_frames, gen):
     """Token-space stand-in for the shared initial-noise pool: [pool_frames, tokens per frame, dim] N(0,1)."""
     tok = cfg["tok_h"] * cfg["tok_w"]
     return round_to(torch.randn((pool_frames, tok, cfg["dim"]), generator=gen, dtype=torch.float32), cfg["dtype"])
+
+
+def make_end_weights(cfg, channels=16, seed=0):
+    """Weights of the model's two ends (patch embedding, output head), N(0, 0.02) like the rest, rounded to
+    cfg["dtype"]; matrices [in, out].  Keys: w_pe [4C, dim], b_pe, m_head [2, dim], w_head [dim, 4C], b_head."""
+    g = torch.Generator(device="cpu").manual_seed(seed + 7777)
+    D, P = cfg["dim"], 4 * channels
+    shapes = OrderedDict(w_pe=(P, D), b_pe=(D,), m_head=(2, D), w_head=(D, P), b_head=(P,))
+    return OrderedDict((k, round_to(0.02 * torch.randn(sh, generator=g, dtype=torch.float32), cfg["dtype"]))
+                       for k, sh in shapes.items())
+
+
+def make_latent(cfg, n_frames, channels, gen):
+    """N(0,1) frame latents [n_frames, 2*tok_h, 2*tok_w, channels], fp32 (latents are kept in fp32)."""
+    return torch.randn((n_frames, 2 * cfg["tok_h"], 2 * cfg["tok_w"], channels), generator=gen, dtype=torch.float32)
