@@ -141,6 +141,60 @@ def cache_ablation(args):
     print(json.dumps(res))
 
 
+def latent_step(args):
+    """Informational: one block pass in latent space on one stage that holds both ends of the model:
+    patch embedding -> 4 layers (+ cache hand-over) -> output head -> Euler update."""
+    from paper_2505_21070_amd import binding as B
+    from paper_2505_21070_amd import synth
+    torch.cuda.set_device(0)
+    C = 16
+    cfg, weights, text, blocks = synth.make_case("wan1p3b_stage", seed=0, n_blocks=1)
+    nf, nc, tok = cfg["block_frames"], cfg["cache_frames"], cfg["tok_h"] * cfg["tok_w"]
+    td = torch.bfloat16
+    stage = B.Stage(B.make_config(cfg, max_abs_frames=64), B.weights_to_device(weights, cfg["dtype"]), text.to("cuda", td).contiguous())
+    ew = synth.make_end_weights(cfg, C, 0)
+    dev = {k: v.to("cuda", td).contiguous() for k, v in ew.items()}
+    dev.update({k: weights["stage"][k].to("cuda", td).contiguous() for k in ("wt1", "bt1", "wt2", "bt2")})
+    ends = B.Ends(cfg, dev, C, nf)
+    gen = torch.Generator().manual_seed(1)
+    lat = synth.make_latent(cfg, nf, C, gen).cuda()
+    stage.forward(blocks[0].to("cuda", td).contiguous(), nf, nf, 625.0)
+    stage.cache_update(0, nc)
+    out = torch.empty((nf * tok, cfg["dim"]), dtype=td, device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+
+    def step(timed=False):
+        if timed: ev[0].record()
+        x = ends.embed(lat)
+        if timed: ev[1].record()
+        stage.forward(x, nf, 0, 500.0, out=out)
+        stage.cache_update(0, nc)
+        if timed: ev[2].record()
+        v = ends.head(out, 500.0, nf)
+        B.euler_step(lat, v, 0.5, 0.48)
+        if timed: ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    step(timed=True)
+    torch.cuda.synchronize()
+    parts = {"embed_ms": ev[0].elapsed_time(ev[1]), "stage_ms": ev[1].elapsed_time(ev[2]), "head_euler_ms": ev[2].elapsed_time(ev[3])}
+    assert torch.isfinite(lat).all()
+    print(json.dumps({"metric": "latent tokens/sec per DiT stage (cached block); attn+FFN TFLOP/s vs bf16 MFMA peak",
+                      "value": nf * tok / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+                      "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+                      "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "wan1p3b_latent (informational: patch embedding + 4 layers + head + Euler step)",
+                                 "layers": cfg["n_layers"], "block_tokens": nf * tok, "latent": [nf, 2 * cfg["tok_h"], 2 * cfg["tok_w"], C]},
+                      "parts": parts}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -158,6 +212,8 @@ def main():
         sys.exit(3)
     if args.workload == "wan1p3b_ablation":
         return cache_ablation(args)
+    if args.workload == "wan1p3b_latent":
+        return latent_step(args)
     from paper_2505_21070_amd import binding as B
     from paper_2505_21070_amd import synth
 

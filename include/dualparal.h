@@ -218,6 +218,49 @@ int dp_noise_assign(const dp_noise_config* cfg, const uint32_t* random_words, in
 int dp_noise_gather(const void* pool, int32_t pool_frames, int64_t frame_bytes, const int32_t* index,
                     int32_t n_frames, void* out, void* hip_stream);
 
+/*
+ * The two ends of the model and the scheduler update (Sec. 2: the frame latent x_t in R^{F x H x W x C}
+ * becomes p = F x H' x W' tokens of hidden size h, the prediction returns in latent shape, and
+ * x_{t-1} = S(eps_t, x_t, t)).  The paper leaves their form to the base model; the reading built here:
+ *   patch embedding : token (f, y, x), frame-major then row-major, is the 1x2x2 latent patch
+ *                     (f, 2y+dy, 2x+dx, c) flattened with dy slowest and c fastest, times w_pe plus b_pe
+ *   output head     : (shift, scale) = m_head[2, dim] + e with e the timestep embedding (sinusoid -> wt1 ->
+ *                     SiLU -> wt2, the stage's weights); LayerNorm(x) * (1 + scale) + shift, times w_head
+ *                     plus b_head, each token's 4*channels outputs scattered to its patch's pixels
+ *   scheduler step  : flow-matching Euler, x <- x + (sigma_next - sigma) * v, sigma = timestep / t_max
+ * Latents and velocities are float32 device arrays [n_frames, 2*tok_h, 2*tok_w, channels]; tokens are
+ * [n_frames*tok_h*tok_w, dim] in the configured storage type.  Like a stage, the handle owns no device
+ * memory: the caller provides the workspace (dp_ends_workspace_bytes, 256-byte aligned) and keeps the
+ * weights alive.  Calls are asynchronous on hip_stream.  DP_BF16 needs dim % 64 == 0 and
+ * 4 * channels % 64 == 0.
+ * Errors: DP_EINVAL (null pointer, sizes outside the configured limits, NaN timestep), DP_ENOMEM
+ * (workspace too small), DP_EHIP.
+ */
+typedef struct dp_ends dp_ends_t;
+typedef struct {
+  int32_t dim, tok_h, tok_w;  /* as in the stage                                                    */
+  int32_t channels;           /* latent channels C; a token carries 4 * C latent values              */
+  int32_t max_frames;         /* frames per call                                                     */
+  int32_t dtype;              /* DP_F32 or DP_BF16: tokens and weights                               */
+  int32_t freq_dim;           /* sinusoidal timestep features, as in the stage                       */
+  float eps;                  /* LayerNorm epsilon                                                   */
+} dp_ends_config;
+typedef struct {              /* device pointers, matrices row-major [in, out], in the storage type  */
+  const void *w_pe, *b_pe;    /* [4*channels, dim], [dim]                                            */
+  const void *m_head;         /* [2, dim]: shift row, scale row                                      */
+  const void *w_head, *b_head;/* [dim, 4*channels], [4*channels]                                     */
+  const void *wt1, *bt1, *wt2, *bt2; /* timestep MLP, the same arrays the stages use                 */
+} dp_ends_weights;
+size_t dp_ends_workspace_bytes(const dp_ends_config* cfg);
+int dp_ends_init(const dp_ends_config* cfg, const dp_ends_weights* weights, void* workspace,
+                 size_t workspace_bytes, void* hip_stream, dp_ends_t** out);
+int dp_embed_forward(dp_ends_t* ends, const float* latent, void* x_out, int32_t n_frames, void* hip_stream);
+int dp_head_forward(dp_ends_t* ends, const void* x_in, float timestep, float* v_out, int32_t n_frames,
+                    void* hip_stream);
+/* x[i] += (sigma_next - sigma) * v[i] for n float32 elements; x and v must not overlap. */
+int dp_euler_step(float* x, const float* v, int64_t n, float sigma, float sigma_next, void* hip_stream);
+void dp_ends_free(dp_ends_t* ends);
+
 /* Test hook: copies an internal result to `dst` as float32, token-major [rows, dim].
  *   what : DP_PEEK_*; layer is used by the K / V / cache / modulation peeks, the others refer to the
  *          last layer the last forward ran (they need cfg.debug_taps for X_SELF / X_CROSS).

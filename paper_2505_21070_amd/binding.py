@@ -85,6 +85,31 @@ _lib.dp_noise_assign.argtypes = [C.POINTER(NoiseConfig), C.POINTER(C.c_uint32), 
                                  C.c_int64, C.POINTER(C.c_int64)]
 _lib.dp_noise_gather.restype = C.c_int
 _lib.dp_noise_gather.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+class EndsConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("dim", "tok_h", "tok_w", "channels", "max_frames", "dtype", "freq_dim")] + \
+               [("eps", C.c_float)]
+
+
+ENDS_FIELDS = ("w_pe", "b_pe", "m_head", "w_head", "b_head", "wt1", "bt1", "wt2", "bt2")
+
+
+class EndsWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ENDS_FIELDS]
+
+
+_lib.dp_ends_workspace_bytes.restype = C.c_size_t
+_lib.dp_ends_workspace_bytes.argtypes = [C.POINTER(EndsConfig)]
+_lib.dp_ends_init.restype = C.c_int
+_lib.dp_ends_init.argtypes = [C.POINTER(EndsConfig), C.POINTER(EndsWeights), C.c_void_p, C.c_size_t, C.c_void_p,
+                              C.POINTER(C.c_void_p)]
+_lib.dp_embed_forward.restype = C.c_int
+_lib.dp_embed_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+_lib.dp_head_forward.restype = C.c_int
+_lib.dp_head_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_int32, C.c_void_p]
+_lib.dp_euler_step.restype = C.c_int
+_lib.dp_euler_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_float, C.c_void_p]
+_lib.dp_ends_free.restype = None
+_lib.dp_ends_free.argtypes = [C.c_void_p]
 _lib.dp_pipeline_simulate.restype = C.c_int
 _lib.dp_pipeline_simulate.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
 _lib.dp_probe_mfma_bf16.restype = C.c_int
@@ -240,6 +265,70 @@ def blockwise_schedule(T, block_num, num_b, num_c, first_block_frames=0, t_max=1
 
 def bubble_ratio(n_devices, T, block_num, order="reverse"):
     return float(_lib.dp_bubble_ratio(n_devices, T, block_num, ORDER[order]))
+
+
+class Ends:
+    """Patch embedding and output head of the model on the current device.  weights: dict of device tensors in
+    the storage dtype with ENDS_FIELDS (the timestep MLP arrays are the stage's)."""
+
+    def __init__(self, cfg, weights, channels, max_frames, stream=None):
+        dt = DP_BF16 if cfg["dtype"] == "bf16" else DP_F32
+        self.config = EndsConfig(cfg["dim"], cfg["tok_h"], cfg["tok_w"], channels, max_frames, dt, cfg["freq_dim"], cfg["eps"])
+        self.torch_dtype = torch.bfloat16 if dt == DP_BF16 else torch.float32
+        self.tok, self.dim, self.channels = cfg["tok_h"] * cfg["tok_w"], cfg["dim"], channels
+        self.frame_shape = (2 * cfg["tok_h"], 2 * cfg["tok_w"], channels)
+        D, P, fd = cfg["dim"], 4 * channels, cfg["freq_dim"]
+        shapes = dict(w_pe=(P, D), b_pe=(D,), m_head=(2, D), w_head=(D, P), b_head=(P,), wt1=(fd, D), bt1=(D,),
+                      wt2=(D, D), bt2=(D,))
+        ew = EndsWeights()
+        for n in ENDS_FIELDS:
+            t = weights[n]
+            assert t.is_cuda and t.dtype == self.torch_dtype and t.is_contiguous() and tuple(t.shape) == shapes[n], n
+            setattr(ew, n, t.data_ptr())
+        self._keep = weights
+        nbytes = _lib.dp_ends_workspace_bytes(C.byref(self.config))
+        if nbytes == 0:
+            raise DualParalError(DP_EINVAL, "dp_ends_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        h = C.c_void_p()
+        self._h = None
+        _check(_lib.dp_ends_init(C.byref(self.config), C.byref(ew), self.workspace.data_ptr(), nbytes,
+                                 _stream_handle(stream), C.byref(h)), "dp_ends_init")
+        self._h = h
+
+    def embed(self, latent, stream=None):
+        n = latent.shape[0]
+        assert latent.is_cuda and latent.dtype == torch.float32 and latent.is_contiguous() and tuple(latent.shape[1:]) == self.frame_shape
+        out = torch.empty((n * self.tok, self.dim), dtype=self.torch_dtype, device=latent.device)
+        _check(_lib.dp_embed_forward(self._h, latent.data_ptr(), out.data_ptr(), n, _stream_handle(stream)), "dp_embed_forward")
+        return out
+
+    def head(self, x, timestep, n_frames, stream=None):
+        assert x.is_cuda and x.dtype == self.torch_dtype and x.is_contiguous() and tuple(x.shape) == (n_frames * self.tok, self.dim)
+        v = torch.empty((n_frames,) + self.frame_shape, dtype=torch.float32, device=x.device)
+        _check(_lib.dp_head_forward(self._h, x.data_ptr(), float(timestep), v.data_ptr(), n_frames, _stream_handle(stream)),
+               "dp_head_forward")
+        return v
+
+    def close(self):
+        if self._h is not None:
+            _lib.dp_ends_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def euler_step(x, v, sigma, sigma_next, stream=None):
+    """In place: x += (sigma_next - sigma) * v (float32 device tensors of equal size)."""
+    assert x.is_cuda and v.is_cuda and x.dtype == v.dtype == torch.float32 and x.is_contiguous() and v.is_contiguous()
+    assert x.numel() == v.numel()
+    _check(_lib.dp_euler_step(x.data_ptr(), v.data_ptr(), x.numel(), float(sigma), float(sigma_next), _stream_handle(stream)),
+           "dp_euler_step")
+    return x
 
 
 def pipeline_simulate(n_devices, T, block_num, order="reverse"):

@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdualparal.so")
-SOURCES = ["stage.hip", "schedule.cpp", "elementwise.hip", "gemm_f32.hip", "attn_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "probe.hip"]
+SOURCES = ["stage.hip", "schedule.cpp", "elementwise.hip", "gemm_f32.hip", "attn_f32.hip", "gemm_bf16.hip", "attn_bf16.hip", "probe.hip", "ends.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wno-unused-value",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
