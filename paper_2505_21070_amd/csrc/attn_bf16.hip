@@ -19,11 +19,11 @@
 // online softmax that raises m whenever a tile exceeds it and rescales O^T.
 //
 // Work split: a block of 8 wavefronts owns QG * 32 queries of one head.  Two shapes are built.
-// QG = 4, KG = 2 (short key ranges, i.e. cross-attention): wavefront w handles query tile w & 3 against
-// key group w >> 2 (first / second half of the key tiles); the two groups stream their own K / V^T tiles
-// and are merged through LDS at the end, which halves the length of a block.  QG = 8, KG = 1 (long key
-// ranges): all 8 wavefronts share every K / V^T tile, so a tile brought into LDS serves 256 queries and
-// the LDS fill traffic per query halves.  Tiles hold 64 keys, are double-buffered and are loaded
+// QG = 4, KG = 2 (few queries or very few keys): wavefront w handles query tile w & 3 against key group
+// w >> 2 (first / second half of the key tiles); the two groups stream their own K / V^T tiles and are
+// merged through LDS at the end, which halves the length of a block.  QG = 8, KG = 1 (everything else,
+// self- and cross-attention at full size): all 8 wavefronts share every K / V^T tile, so a tile brought
+// into LDS serves 256 queries and the LDS fill traffic per query halves.  Tiles hold 64 keys, are double-buffered and are loaded
 // HBM -> LDS directly.  Two wavefronts per SIMD hide each other's LDS and matrix-core latencies.
 //
 // Grid: one block fits per compute unit, so a grid runs in rounds of 256 blocks.  The work ids that
@@ -401,9 +401,10 @@ void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, i
                       int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
                       int h, int d, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st) {
   if (S <= 0 || L <= 0) return;
-  // Long key ranges: 256 queries per block share every K / V^T tile (half the LDS fill traffic per
-  // query).  Short ones (cross-attention): 128 queries per block with the keys split over two groups.
-  const bool wide = L >= 2048 && ((S + 255) / 256) * h >= 128;
+  // 256 queries per block share every K / V^T tile (half the LDS fill traffic per query) whenever that
+  // still gives the grid half a round of blocks and the key range a few tiles; otherwise 128 queries per
+  // block with the keys split over two groups, which halves the length of a block.
+  const bool wide = L >= 256 && ((S + 255) / 256) * h >= 128;
 #define ATTN_ARGS q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, h, out, ldo, scratch, st
   if (d == 128) { if (wide) launch_attn_cfg<128, 8, 1>(ATTN_ARGS); else launch_attn_cfg<128, 4, 2>(ATTN_ARGS); }
   else { if (wide) launch_attn_cfg<64, 8, 1>(ATTN_ARGS); else launch_attn_cfg<64, 4, 2>(ATTN_ARGS); }
