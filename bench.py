@@ -23,9 +23,10 @@ PEAK_FP32_TFLOPS = 157.3      # fp32 vector
 PEAK_HBM_GBS = 8000.0         # HBM3E, published
 
 # HBM-side bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this command
-# (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for the plain cache-copy kernel of
-# known size; figures and commands in profiles/bench_wan1p3b_stage.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 233.6e6}
+# (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for a plain streaming copy of known
+# size (the stage's fp32 -> bf16 output conversion); figures and commands in
+# profiles/bench_wan1p3b_stage.md.  None where not measured.
+MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 223.4e6}
 
 
 def class_work(cfg, S, Nc):
