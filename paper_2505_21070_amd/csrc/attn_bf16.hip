@@ -310,11 +310,17 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
           v.w = both(a, g4 * 4 + 3, a0, a1);
           *(float4*)(ps + 2 * QB + ((size_t)(a * 8 + g4 * 2 + lg) * QB + ql) * 4) = v;
         }
-    } else if (qi < S) {
+    } else {
+      // O[q][head*HD + c] = O^T[c][q]: a lane holds 4 consecutive channels per register quad.  The 32 x HD
+      // tile of this wavefront goes through LDS (the tile buffers are free; a wavefront only touches its own
+      // rows, and LDS serves a wavefront's accesses in order) so that global memory sees whole rows, 16
+      // bytes per lane.  8-byte units are XOR-swizzled with the row so that the column-wise writes spread
+      // over the banks.
       const float inv = 1.f / lall;
       const float w0 = a0 * inv, w1 = a1 * inv;
-      // O[q][head*HD + c] = O^T[c][q] ; lane holds 4 consecutive c per register quad
-      bf16_t* o = out + qi * ldo + (int64_t)head * HD;
+      constexpr int UPR = HD / 4, CPR = HD / 8, RPI = 64 / CPR;      // units, 16-byte chunks per row; rows per read
+      constexpr int STG0 = KG == 2 ? QG * (DT * 16 + 2) * 64 * 4 / 16 : 0;    // behind the exchange area
+      uint2* stg = (uint2*)(smem + STG0) + qt * 32 * UPR;
 #pragma unroll
       for (int a = 0; a < DT; ++a)
 #pragma unroll
@@ -322,8 +328,18 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
           uint2 pk;
           pk.x = cvt_pk_bf16(both(a, g4 * 4 + 0, w0, w1), both(a, g4 * 4 + 1, w0, w1));
           pk.y = cvt_pk_bf16(both(a, g4 * 4 + 2, w0, w1), both(a, g4 * 4 + 3, w0, w1));
-          *(uint2*)(o + a * 32 + g4 * 8 + lg * 4) = pk;
+          stg[lr * UPR + ((a * 8 + g4 * 2 + lg) ^ (lr & (UPR - 1)))] = pk;
         }
+      const uint4* stg16 = (const uint4*)stg;
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int row = it * RPI + lane / CPR, p = lane % CPR;
+        uint4 dv = stg16[row * CPR + p];
+        // units 2p and 2p+1 of the swizzled row are the halves of chunk p ^ (swizzle >> 1), exchanged for odd rows
+        if (row & 1) dv = make_uint4(dv.z, dv.w, dv.x, dv.y);
+        const int c = p ^ ((row & (UPR - 1)) >> 1);
+        if (q0 + row < S) *(uint4*)(out + (q0 + row) * ldo + (int64_t)head * HD + c * 8) = dv;
+      }
     }
   }
 }
