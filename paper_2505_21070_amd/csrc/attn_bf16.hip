@@ -164,7 +164,7 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
     bool fresh = true;                                  // SAFE: no key seen yet, mrun is a placeholder
 
     if (cnt > 0) load_tile(0, 0);
-    __syncthreads();
+    tile_barrier();
     if (!SAFE && cnt > 0) {
       // reference = maximum over the first 32 keys (all valid: a group's first tile starts below L)
       f32x16 s0;
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
           }
         }
       }
-      __syncthreads();      // the next tile has landed and every wavefront is done with this one
+      tile_barrier();       // the next tile has landed and every wavefront is done with this one
     }
     return fresh;
   };

@@ -27,6 +27,15 @@ template <> struct Elem<bf16_t> {
   static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
 };
 
+// Barrier that publishes an LDS tile which the block's wavefronts loaded together with direct
+// global -> LDS loads.  The compiler orders such a load only against the issuing wavefront's own later LDS
+// reads, not against a barrier, so every wavefront first waits for its outstanding vector-memory loads
+// itself (s_waitcnt vmcnt(0); the other counters are left alone) and then joins the barrier.
+__device__ __forceinline__ void tile_barrier() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt = 0, expcnt = 7 and lgkmcnt = 15 (no wait)
+  __syncthreads();
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -113,7 +113,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   };
   bf16x8 af[2][TM], bfr[2][TN];
   load_tile(0, 0);
-  __syncthreads();
+  tile_barrier();
   load_tile(1, 1);
   read_frags(smem, 0, af[0], bfr[0]);
   for (int kt = 0; kt < KT; ++kt) {
@@ -123,7 +123,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
       if (ks < 3) {
         read_frags(buf, ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
       } else {
-        __syncthreads();
+        tile_barrier();
         load_tile(kt + 2, kt & 1);
         read_frags(smem + ((kt + 1) & 1) * STAGE, 0, af[0], bfr[0]);
       }
