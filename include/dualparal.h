@@ -280,7 +280,8 @@ int dp_stage_peek(dp_stage_t* stage, int32_t what, int32_t layer, float* dst, in
  * recorded events and writes, for each of the DP_PROF_COUNT classes, the summed milliseconds and the
  * number of launches into two host arrays, then stops collecting.  At most 16384 launches are recorded
  * per begin/end pair; later ones are not timed.  Events are host-side objects; no device memory is
- * allocated.  Errors: DP_EINVAL, DP_EHIP. */
+ * allocated.  DP_PROF_CACHE_COPY never reports launches: the cache hand-over moves no data.
+ * Errors: DP_EINVAL, DP_EHIP. */
 enum { DP_PROF_LN = 0, DP_PROF_QKV_GEMM = 1, DP_PROF_NORM_ROPE = 2, DP_PROF_SELF_ATTN = 3,
        DP_PROF_OPROJ_GEMM = 4, DP_PROF_CROSS_Q_GEMM = 5, DP_PROF_CROSS_ATTN = 6, DP_PROF_CROSS_O_GEMM = 7,
        DP_PROF_FFN1_GEMM = 8, DP_PROF_FFN2_GEMM = 9, DP_PROF_CACHE_COPY = 10, DP_PROF_MODULATION = 11,
