@@ -103,6 +103,7 @@ void launch_ln_modulate(const float* x, T* out, int64_t S, int D, float eps, con
   const float plus = plus_one ? 1.f : 0.f;
   if (D <= 256) k_ln_modulate<T, 1><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);
   else if (D <= 2048) k_ln_modulate<T, 8><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);
+  else if (D <= 5120) k_ln_modulate<T, 20><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);
   else k_ln_modulate<T, 32><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);   // D <= 8192
 }
 template void launch_ln_modulate<float>(const float*, float*, int64_t, int, float, const float*, const float*, int, hipStream_t);
