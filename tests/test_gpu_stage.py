@@ -225,13 +225,16 @@ def test_error_paths_leave_gpu_alone():
     assert rc == B.DP_EINVAL and not h.value      # null weights
 
 
-def test_peaked_attention_takes_the_safe_pass():
+@pytest.mark.parametrize("name,over", [("small_bf16", {}),                      # 128-query blocks, one key tile
+                                       ("wide64_bf16", {"text_len": 320}),      # 256-query blocks, 5 key tiles
+                                       ("wide64_bf16", {"text_len": 1100})])    # ... cut into two key ranges + merge
+def test_peaked_attention_takes_the_safe_pass(name, over):
     """Large cross-attention q/k gains make base-2 logits of later keys exceed those of the first 32 keys
     by far more than 2^100, so the fixed-reference fast pass of the attention kernel overflows and the
     kernel must recompute those blocks with the classical online softmax.  The kernel's output is
     checked against a float64 softmax over the very q, K, V it read (peeked from the library), because
     at such logit ranges the bf16 rounding of q and K, not the kernel, dominates any end-to-end error."""
-    cfg, w, text, blocks = synth.make_case("small_bf16", seed=8, strong_gate=True)
+    cfg, w, text, blocks = synth.make_case(name, seed=8, strong_gate=True, **over)
     for lw in w["layers"]:
         for k in ("cgq", "cgk"):
             lw[k] = synth.round_to(lw[k] * 12.0, "bf16")
