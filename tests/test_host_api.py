@@ -115,3 +115,29 @@ def test_pipeline_simulation_matches_oracle(B):
     assert B._lib.dp_pipeline_simulate(0, 5, 5, 0, C.byref(mk), C.byref(bub)) == B.DP_EINVAL
     assert B._lib.dp_pipeline_simulate(2, 5, 5, 7, C.byref(mk), C.byref(bub)) == B.DP_EINVAL
     assert B._lib.dp_pipeline_simulate(2, 5, 5, 0, None, C.byref(bub)) == B.DP_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_product_never_touches_the_oracle():
+    """The oracle is test infrastructure: nothing under the package imports, loads or runs it, and bench.py only
+    does so inside its cpu_baseline leg."""
+    pkg = os.path.join(ROOT, "paper_2505_21070_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "synth.py", os.path.join(dirpath, f)
+    synth_src = open(os.path.join(pkg, "synth.py")).read()
+    assert "import oracle" not in synth_src and "from oracle" not in synth_src
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    head, _, rest = bench.partition("def cpu_baseline(")
+    body, _, tail = rest.partition("\ndef ")
+    assert "oracle" in body                                   # the baseline leg is where it is used ...
+    assert "from oracle" not in head and "import oracle" not in head
+    assert "from oracle" not in tail and "import oracle" not in tail      # ... and nowhere else
