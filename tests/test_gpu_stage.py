@@ -255,3 +255,35 @@ def test_peaked_attention_takes_the_safe_pass(name, over):
         ref[:, sl] = (p / p.sum(1, keepdims=True)) @ vt[:, sl]
     assert spread > 110.0, spread                                # beyond what the fast pass can hold
     check("peaked/cross_attn", got, ref, "bf16")
+
+
+@pytest.mark.parametrize("name,seed", [("tiny", 21), ("small_bf16", 22)])
+def test_random_sequence_of_blocks_and_cache_ranges(name, seed):
+    """A random walk through the API: blocks of varying length, arbitrary retained frame ranges (which decide
+    whether the next block's keys go before or after the cache in the library's buffer), cleared caches,
+    repeated cache updates; every output is compared with the oracle doing the same."""
+    cfg, w, text, _ = synth.make_case(name, seed=seed, strong_gate=True)
+    max_b, max_c = 4, 3
+    g = gpu_stage(cfg, w, text, max_block_frames=max_b, max_cache_frames=max_c, max_abs_frames=64)
+    o = oracle_stage(cfg, w, text)
+    rng = np.random.default_rng(seed)
+    gen = torch.Generator().manual_seed(seed)
+    last = 0
+    for step in range(14):
+        nf = int(rng.integers(1, max_b + 1))
+        f0 = int(rng.integers(0, 64 - nf))
+        t = float(rng.integers(1, 1000))
+        x = synth.make_block(cfg, nf, gen)
+        y = g.forward(to_dev(x, cfg), nf, f0, t)
+        r = o.forward(x.numpy(), nf, f0, t)
+        check(f"{name}/walk{step}", to_np(y), r, cfg["dtype"])
+        last = nf
+        for _ in range(int(rng.integers(1, 3))):              # one or two cache updates; the last one counts
+            n = int(rng.integers(0, min(max_c, last) + 1))
+            first = int(rng.integers(0, last - n + 1))
+            g.cache_update(first, n)
+            o.cache_update(first, n)
+        if o.cache[0] is not None:
+            li = cfg["n_layers"] - 1
+            check(f"{name}/walk{step}/cache_k", to_np(g.peek("cache_k", li)), o.cache[li][0], cfg["dtype"])
+            check(f"{name}/walk{step}/cache_v", to_np(g.peek("cache_v", li)), o.cache[li][1], cfg["dtype"])
