@@ -155,49 +155,57 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   if constexpr (EPI != EPI_RESID) {
     constexpr int UPR = BN / 4;                          // 8-byte units (4 bf16) per LDS row
     constexpr int CPR = BN / 8, RPI = 64 / CPR;          // 16-byte chunks per row, rows per wavefront read
+    // the whole tile at once if it fits the two operand buffers, else one wavefront row (WM rows) per pass
+    constexpr int SP = (BM * BN * 2 <= (BM + BN) * 256) ? 1 : WGM, RP = BM / SP;
     uint2* l8 = (uint2*)smem;
-    __syncthreads();                                     // every wavefront is done with the operand tiles
 #pragma unroll
-    for (int j = 0; j < TN; ++j)
+    for (int pass = 0; pass < SP; ++pass) {
+      __syncthreads();                                   // the operand tiles / the previous pass are done with
+      if (SP == 1 || wm == pass) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int nl = wn * WN + j * 32 + q * 8 + lg * 4;
-        float bv[4] = {0.f, 0.f, 0.f, 0.f};
-        if (bias && n0 + nl < N) {
-          const uint2 b4 = *(const uint2*)(bias + n0 + nl);
-          bv[0] = bf16_to_f32((bf16_t)(b4.x & 0xffff)); bv[1] = bf16_to_f32((bf16_t)(b4.x >> 16));
-          bv[2] = bf16_to_f32((bf16_t)(b4.y & 0xffff)); bv[3] = bf16_to_f32((bf16_t)(b4.y >> 16));
-        }
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int row = wm * WM + i * 32 + lr;
-          float v[4];
+          for (int q = 0; q < 4; ++q) {
+            const int nl = wn * WN + j * 32 + q * 8 + lg * 4;
+            float bv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (bias && n0 + nl < N) {
+              const uint2 b4 = *(const uint2*)(bias + n0 + nl);
+              bv[0] = bf16_to_f32((bf16_t)(b4.x & 0xffff)); bv[1] = bf16_to_f32((bf16_t)(b4.x >> 16));
+              bv[2] = bf16_to_f32((bf16_t)(b4.y & 0xffff)); bv[3] = bf16_to_f32((bf16_t)(b4.y >> 16));
+            }
 #pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            v[t] = acc[i][j][q * 4 + t] + bv[t];
-            if (EPI == EPI_GELU) v[t] = gelu_tanh_fast(v[t]);
+            for (int i = 0; i < TM; ++i) {
+              const int row = (SP == 1 ? wm * WM : 0) + i * 32 + lr;      // row inside this pass
+              float v[4];
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {
+                v[t] = acc[i][j][q * 4 + t] + bv[t];
+                if (EPI == EPI_GELU) v[t] = gelu_tanh_fast(v[t]);
+              }
+              uint2 pk;
+              pk.x = cvt_pk_bf16(v[0], v[1]);
+              pk.y = cvt_pk_bf16(v[2], v[3]);
+              l8[row * UPR + ((nl >> 2) ^ (row & 31))] = pk;
+            }
           }
-          uint2 pk;
-          pk.x = cvt_pk_bf16(v[0], v[1]);
-          pk.y = cvt_pk_bf16(v[2], v[3]);
-          l8[row * UPR + ((nl >> 2) ^ (row & 31))] = pk;
-        }
       }
-    __syncthreads();
+      __syncthreads();
 #pragma unroll
-    for (int it = 0; it < BM / NW / RPI; ++it) {
-      const int row = wave * (BM / NW) + it * RPI + lane / CPR, p = lane % CPR;
-      uint4 d = smem[row * CPR + p];
-      // the chunk read holds units 2p and 2p+1 of the swizzled row, i.e. the two halves of logical
-      // chunk p ^ ((row & 31) >> 1), exchanged when the row index is odd
-      if (row & 1) d = make_uint4(d.z, d.w, d.x, d.y);
-      const int64_t m = m0 + row, n = n0 + (p ^ ((row & 31) >> 1)) * 8;
-      if (m < M && n < N) *(uint4*)((bf16_t*)e.out + m * e.ldo + n) = d;
+      for (int it = 0; it < RP / NW / RPI; ++it) {
+        const int row = wave * (RP / NW) + it * RPI + lane / CPR, p = lane % CPR;
+        uint4 d = smem[row * CPR + p];
+        // the chunk read holds units 2p and 2p+1 of the swizzled row, i.e. the two halves of logical
+        // chunk p ^ ((row & 31) >> 1), exchanged when the row index is odd
+        if (row & 1) d = make_uint4(d.z, d.w, d.x, d.y);
+        const int64_t m = m0 + pass * RP + row, n = n0 + (p ^ ((row & 31) >> 1)) * 8;
+        if (m < M && n < N) *(uint4*)((bf16_t*)e.out + m * e.ldo + n) = d;
+      }
     }
   } else {
     // residual stream: x[m, n] += gate[n] * (acc + bias[n]) in fp32; one pass per wavefront row of the
     // block tile (WM rows x BN columns of floats fit in LDS at a time)
     constexpr int CPR = BN / 4, RPI = 64 / CPR;          // 16-byte chunks (4 floats) per row
+    static_assert(WM * BN * 4 <= (BM + BN) * 256, "a wavefront row of fp32 results must fit the operand buffers");
     float4* l16 = (float4*)smem;
 #pragma unroll
     for (int pass = 0; pass < WGM; ++pass) {
@@ -247,7 +255,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   }
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, bool RESID_OK = true>
 static void launch_cfg(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
                        int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
   constexpr int NT = WGM * WGN * 64;
@@ -257,13 +265,14 @@ static void launch_cfg(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t l
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_STORE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     (void)hipFuncSetAttribute((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_GELU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if constexpr (RESID_OK)
+      (void)hipFuncSetAttribute((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
   dim3 grid((unsigned)((tm * tn + 7) / 8 * 8));
   if (epi == EPI_STORE) k_gemm_bf16<BM, BN, WGM, WGN, EPI_STORE><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
   else if (epi == EPI_GELU) k_gemm_bf16<BM, BN, WGM, WGN, EPI_GELU><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
-  else k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
+  else if constexpr (RESID_OK) k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
 }
 
 static double cu_fill(int64_t blocks) { return (double)blocks / (double)(((blocks + 255) / 256) * 256); }
@@ -272,13 +281,18 @@ void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ld
                       int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
   if (M <= 0 || N <= 0) return;
   // One block per CU at a time, so a launch costs ceil(blocks / 256) rounds of one block's duration.
-  // 256x256 tiles have the most operand reuse; 192x256 tiles trade a little of it for more blocks when
-  // that fills the last round better; tiny problems take 128x128 tiles.
+  // 256x256 tiles are the default; 192x256 tiles (0.82 of their duration) and 320x256 tiles (1.25, fewer
+  // operand bytes per flop; store epilogues only, and only where the rows it reads beyond M stay inside
+  // the 256-row padding the caller guarantees) are taken when they need fewer or cheaper rounds; tiny
+  // problems take 128x128 tiles.
   const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t192 = ((M + 191) / 192) * ((N + 255) / 256);
+  const int64_t t320 = ((M + 319) / 320) * ((N + 255) / 256);
   if (t256 < 64) { launch_cfg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
   const double cost256 = (double)((t256 + 255) / 256), cost192 = 0.82 * (double)((t192 + 255) / 256);
-  (void)cu_fill;
+  const bool ok320 = epi != EPI_RESID && (M + 319) / 320 * 320 <= (M + 255) / 256 * 256;
+  const double cost320 = ok320 ? 1.25 * (double)((t320 + 255) / 256) : 1e30;
+  if (cost320 < cost256 && cost320 < cost192) { launch_cfg<320, 256, 2, 4, false>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
   if (cost192 < cost256) launch_cfg<192, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st);
   else launch_cfg<256, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st);
 }
