@@ -38,9 +38,10 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
-  constexpr int IA = BM * 8 / NT, IB = BN * 8 / NT;      // wavefront load instructions per k-tile (64 chunks each)
+  constexpr int IA = (BM * 8 + NT - 1) / NT, IB = BN * 8 / NT;   // wavefront load instructions per k-tile (64 chunks each)
+  constexpr bool A_RAGGED = BM * 8 % NT != 0;                  // the last wavefronts' share of the A tile is shorter
   constexpr int STAGE = (BM + BN) * 8;                   // 16-byte chunks per LDS buffer
-  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/thread mismatch");
+  static_assert(BM * 8 % 64 == 0 && BN * 8 % NT == 0, "tile/thread mismatch");
   extern __shared__ uint4 smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -79,7 +80,8 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
     uint4* base = smem + bufi * STAGE;
 #pragma unroll
     for (int i = 0; i < IA; ++i)
-      __builtin_amdgcn_global_load_lds((glb_void_t*)(gA[i] + t), (lds_void_t*)(base + (wave * IA + i) * 64), 16, 0, 0);
+      if (!A_RAGGED || (wave * IA + i) * 64 < BM * 8)
+        __builtin_amdgcn_global_load_lds((glb_void_t*)(gA[i] + t), (lds_void_t*)(base + (wave * IA + i) * 64), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < IB; ++i)
       __builtin_amdgcn_global_load_lds((glb_void_t*)(gB[i] + t), (lds_void_t*)(base + BM * 8 + (wave * IB + i) * 64), 16, 0, 0);
@@ -202,53 +204,60 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
       }
     }
   } else {
-    // residual stream: x[m, n] += gate[n] * (acc + bias[n]) in fp32; one pass per wavefront row of the
-    // block tile (WM rows x BN columns of floats fit in LDS at a time)
+    // residual stream: x[m, n] += gate[n] * (acc + bias[n]) in fp32.  Passes over the wavefront rows of the
+    // block tile and, inside one, over groups of GI 32-row accumulator tiles: as many as fit in LDS as floats
     constexpr int CPR = BN / 4, RPI = 64 / CPR;          // 16-byte chunks (4 floats) per row
-    static_assert(WM * BN * 4 <= (BM + BN) * 256, "a wavefront row of fp32 results must fit the operand buffers");
+    constexpr int GI_FIT = (BM + BN) * 256 / (32 * BN * 4), GI = GI_FIT < TM ? GI_FIT : TM;
+    static_assert(GI >= 1, "one 32-row tile of fp32 results must fit the operand buffers");
     float4* l16 = (float4*)smem;
 #pragma unroll
     for (int pass = 0; pass < WGM; ++pass) {
-      __syncthreads();
-      if (wm == pass) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+      for (int i0 = 0; i0 < TM; i0 += GI) {
+        const int gi = TM - i0 < GI ? TM - i0 : GI;      // accumulator tiles in this group
+        __syncthreads();
+        if (wm == pass) {
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int nl = wn * WN + j * 32 + q * 8 + lg * 4;
-            float bv[4] = {0.f, 0.f, 0.f, 0.f};
-            float4 gv = make_float4(1.f, 1.f, 1.f, 1.f);
-            if (n0 + nl < N) {
-              if (bias) {
-                const uint2 b4 = *(const uint2*)(bias + n0 + nl);
-                bv[0] = bf16_to_f32((bf16_t)(b4.x & 0xffff)); bv[1] = bf16_to_f32((bf16_t)(b4.x >> 16));
-                bv[2] = bf16_to_f32((bf16_t)(b4.y & 0xffff)); bv[3] = bf16_to_f32((bf16_t)(b4.y >> 16));
+          for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const int nl = wn * WN + j * 32 + q * 8 + lg * 4;
+              float bv[4] = {0.f, 0.f, 0.f, 0.f};
+              float4 gv = make_float4(1.f, 1.f, 1.f, 1.f);
+              if (n0 + nl < N) {
+                if (bias) {
+                  const uint2 b4 = *(const uint2*)(bias + n0 + nl);
+                  bv[0] = bf16_to_f32((bf16_t)(b4.x & 0xffff)); bv[1] = bf16_to_f32((bf16_t)(b4.x >> 16));
+                  bv[2] = bf16_to_f32((bf16_t)(b4.y & 0xffff)); bv[3] = bf16_to_f32((bf16_t)(b4.y >> 16));
+                }
+                if (e.gate) gv = *(const float4*)(e.gate + n0 + nl);
               }
-              if (e.gate) gv = *(const float4*)(e.gate + n0 + nl);
-            }
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-              const int row = i * 32 + lr;
-              float4 v;
-              v.x = gv.x * (acc[i][j][q * 4 + 0] + bv[0]);
-              v.y = gv.y * (acc[i][j][q * 4 + 1] + bv[1]);
-              v.z = gv.z * (acc[i][j][q * 4 + 2] + bv[2]);
-              v.w = gv.w * (acc[i][j][q * 4 + 3] + bv[3]);
-              l16[row * CPR + ((nl >> 2) ^ (row & 15))] = v;
+              for (int ii = 0; ii < GI; ++ii) {
+                if (i0 + ii < TM) {
+                  const int row = ii * 32 + lr;
+                  float4 v;
+                  v.x = gv.x * (acc[i0 + ii][j][q * 4 + 0] + bv[0]);
+                  v.y = gv.y * (acc[i0 + ii][j][q * 4 + 1] + bv[1]);
+                  v.z = gv.z * (acc[i0 + ii][j][q * 4 + 2] + bv[2]);
+                  v.w = gv.w * (acc[i0 + ii][j][q * 4 + 3] + bv[3]);
+                  l16[row * CPR + ((nl >> 2) ^ (row & 15))] = v;
+                }
+              }
             }
+        }
+        __syncthreads();
+        // gi * 32 rows, shared out over the wavefronts RPI rows per read
+        for (int r = wave * RPI; r < gi * 32; r += NW * RPI) {
+          const int row = r + lane / CPR, p = lane % CPR;
+          const float4 v = l16[row * CPR + p];
+          const int64_t m = m0 + pass * WM + i0 * 32 + row, n = n0 + (p ^ (row & 15)) * 4;
+          if (m < M && n < N) {
+            float4* x = (float4*)(e.resid + m * e.ldr + n);
+            float4 xv = *x;
+            xv.x += v.x; xv.y += v.y; xv.z += v.z; xv.w += v.w;
+            *x = xv;
           }
-      }
-      __syncthreads();
-#pragma unroll
-      for (int it = 0; it < WM / NW / RPI; ++it) {
-        const int row = wave * (WM / NW) + it * RPI + lane / CPR, p = lane % CPR;
-        const float4 v = l16[row * CPR + p];
-        const int64_t m = m0 + pass * WM + row, n = n0 + (p ^ (row & 15)) * 4;
-        if (m < M && n < N) {
-          float4* x = (float4*)(e.resid + m * e.ldr + n);
-          float4 xv = *x;
-          xv.x += v.x; xv.y += v.y; xv.z += v.z; xv.w += v.w;
-          *x = xv;
         }
       }
     }
@@ -275,24 +284,27 @@ static void launch_cfg(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t l
   else if constexpr (RESID_OK) k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
 }
 
-static double cu_fill(int64_t blocks) { return (double)blocks / (double)(((blocks + 255) / 256) * 256); }
-
 void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
                       int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
   if (M <= 0 || N <= 0) return;
   // One block per CU at a time, so a launch costs ceil(blocks / 256) rounds of one block's duration.
-  // 256x256 tiles are the default; 192x256 tiles (0.82 of their duration) and 320x256 tiles (1.25, fewer
-  // operand bytes per flop; store epilogues only, and only where the rows it reads beyond M stay inside
-  // the 256-row padding the caller guarantees) are taken when they need fewer or cheaper rounds; tiny
-  // problems take 128x128 tiles.
+  // 256x256 tiles are the default.  Other shapes are taken when rounds x relative duration comes out lower:
+  // 192x256 (0.82 of a 256x256 tile), 160x256 (0.79; 1 x 8 wavefronts, more LDS reads per MFMA, but e.g. 39 x 6
+  // tiles fill one round where 33 x 6 leave 58 CUs idle) and 320x256 (1.25, fewer operand bytes per flop).
+  // The 160- and 320-row tiles read rows beyond M up to their own multiple, so they are used only where
+  // that stays inside the 256-row padding the caller guarantees.  Tiny problems take 128x128 tiles.
   const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t192 = ((M + 191) / 192) * ((N + 255) / 256);
+  const int64_t t160 = ((M + 159) / 160) * ((N + 255) / 256);
   const int64_t t320 = ((M + 319) / 320) * ((N + 255) / 256);
   if (t256 < 64) { launch_cfg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
+  const int64_t mpad = (M + 255) / 256 * 256;
   const double cost256 = (double)((t256 + 255) / 256), cost192 = 0.82 * (double)((t192 + 255) / 256);
-  const bool ok320 = epi != EPI_RESID && (M + 319) / 320 * 320 <= (M + 255) / 256 * 256;
-  const double cost320 = ok320 ? 1.25 * (double)((t320 + 255) / 256) : 1e30;
-  if (cost320 < cost256 && cost320 < cost192) { launch_cfg<320, 256, 2, 4, false>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
-  if (cost192 < cost256) launch_cfg<192, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st);
-  else launch_cfg<256, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st);
+  const double cost160 = (M + 159) / 160 * 160 <= mpad ? 0.79 * (double)((t160 + 255) / 256) : 1e30;
+  const double cost320 = (M + 319) / 320 * 320 <= mpad ? 1.25 * (double)((t320 + 255) / 256) : 1e30;
+  const double best = fmin(fmin(cost256, cost192), fmin(cost160, cost320));
+  if (best == cost256) { launch_cfg<256, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
+  if (best == cost160) { launch_cfg<160, 256, 1, 8>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
+  if (best == cost320) { launch_cfg<320, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
+  launch_cfg<192, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st);
 }
