@@ -304,28 +304,38 @@ void launch_sinusoid(float t, int freq_dim, float* out, hipStream_t st) {
   k_sinusoid<<<cdiv(freq_dim / 2, 64), 64, 0, st>>>(t, freq_dim, out);
 }
 
-// y[n] = sum_k act(x[k]) W[k,n] + b[n].  A block owns 64 output columns; its 16 wavefronts each take every
-// 16th row of W (coalesced 64-column reads) and the partial sums meet in LDS.
+// Matrix-vector products of the timestep MLP.  A block owns 64 output columns and one of gridDim.y slices of the
+// K rows; its 16 wavefronts each take every 16th row of the slice (coalesced 64-column reads) and the partial
+// sums meet in LDS.  The block writes its slice's partial result y[slice][n] without bias: whoever consumes the
+// vector adds the slices up in index order (so the result does not depend on timing) together with the bias.
+// The input is such a sliced vector itself: x[k] = act(sum_p x[p][k] + xbias[k]).
 template <typename T>
-__global__ __launch_bounds__(1024) void k_gemv(const float* __restrict__ x, int K, const T* __restrict__ W,
-                                               const T* __restrict__ b, int N, int silu_in,
-                                               float* __restrict__ y) {
-  extern __shared__ float xs[];            // K activations, then 16 x 64 partial sums
-  float* red = xs + K;
-  for (int k = threadIdx.x; k < K; k += 1024) { const float v = x[k]; xs[k] = silu_in ? v / (1.0f + expf(-v)) : v; }
+__global__ __launch_bounds__(1024) void k_gemv(const float* __restrict__ x, int x_parts, int x_stride,
+                                               const T* __restrict__ xbias, int K, const T* __restrict__ W, int N,
+                                               int silu_in, float* __restrict__ y) {
+  extern __shared__ float xs[];            // this slice's activations, then 16 x 64 partial sums
+  const int KS = gridDim.y, ks = blockIdx.y;
+  const int k0 = (int)((int64_t)K * ks / KS), Kb = (int)((int64_t)K * (ks + 1) / KS) - k0;
+  float* red = xs + Kb;
+  for (int k = threadIdx.x; k < Kb; k += 1024) {
+    float v = xbias ? Elem<T>::ld(xbias + k0 + k) : 0.f;
+    for (int p = 0; p < x_parts; ++p) v += x[(int64_t)p * x_stride + k0 + k];
+    xs[k] = silu_in ? v / (1.0f + expf(-v)) : v;
+  }
   __syncthreads();
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + tx;
+  const T* Wb = W + (int64_t)k0 * N;
   float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
   if (n < N) {
     int k = ty;
-    for (; k + 48 < K; k += 64) {
-      a0 += xs[k] * Elem<T>::ld(W + (int64_t)k * N + n);
-      a1 += xs[k + 16] * Elem<T>::ld(W + (int64_t)(k + 16) * N + n);
-      a2 += xs[k + 32] * Elem<T>::ld(W + (int64_t)(k + 32) * N + n);
-      a3 += xs[k + 48] * Elem<T>::ld(W + (int64_t)(k + 48) * N + n);
+    for (; k + 48 < Kb; k += 64) {
+      a0 += xs[k] * Elem<T>::ld(Wb + (int64_t)k * N + n);
+      a1 += xs[k + 16] * Elem<T>::ld(Wb + (int64_t)(k + 16) * N + n);
+      a2 += xs[k + 32] * Elem<T>::ld(Wb + (int64_t)(k + 32) * N + n);
+      a3 += xs[k + 48] * Elem<T>::ld(Wb + (int64_t)(k + 48) * N + n);
     }
-    for (; k < K; k += 16) a0 += xs[k] * Elem<T>::ld(W + (int64_t)k * N + n);
+    for (; k < Kb; k += 16) a0 += xs[k] * Elem<T>::ld(Wb + (int64_t)k * N + n);
   }
   red[ty * 64 + tx] = (a0 + a1) + (a2 + a3);
   __syncthreads();
@@ -333,24 +343,42 @@ __global__ __launch_bounds__(1024) void k_gemv(const float* __restrict__ x, int 
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) sum += red[i * 64 + tx];
-    y[n] = sum + (b ? Elem<T>::ld(b + n) : 0.f);
+    y[(int64_t)ks * N + n] = sum;
   }
 }
+int gemv_slices(int K, int N) {
+  int ks = (256 + cdiv(N, 64) - 1) / cdiv(N, 64);     // enough blocks for the 256 CUs
+  if (ks > GEMV_MAX_SLICES) ks = GEMV_MAX_SLICES;
+  while (ks > 1 && K / ks < 64) --ks;
+  return ks < 1 ? 1 : ks;
+}
 template <typename T>
-void launch_gemv(const float* x, int K, const T* W, const T* b, int N, int silu_in, float* y, hipStream_t st) {
-  k_gemv<T><<<cdiv(N, 64), 1024, (size_t)(K + 1024) * sizeof(float), st>>>(x, K, W, b, N, silu_in, y);
+void launch_gemv(const float* x, int x_parts, int x_stride, const T* xbias, int K, const T* W, int N, int silu_in,
+                 float* y, hipStream_t st) {
+  const int ks = gemv_slices(K, N);
+  k_gemv<T><<<dim3(cdiv(N, 64), ks), 1024, (size_t)(cdiv(K, ks) + 1 + 1024) * sizeof(float), st>>>(
+      x, x_parts, x_stride, xbias, K, W, N, silu_in, y);
 }
-template void launch_gemv<float>(const float*, int, const float*, const float*, int, int, float*, hipStream_t);
-template void launch_gemv<bf16_t>(const float*, int, const bf16_t*, const bf16_t*, int, int, float*, hipStream_t);
+template void launch_gemv<float>(const float*, int, int, const float*, int, const float*, int, int, float*, hipStream_t);
+template void launch_gemv<bf16_t>(const float*, int, int, const bf16_t*, int, const bf16_t*, int, int, float*, hipStream_t);
 
-__global__ void k_mod_add(const float* __restrict__ mtab, const float* __restrict__ e0,
-                          float* __restrict__ mod, int L, int n) {
+// mod[l, i] = mtab[l, i] + sum_p e[p][i] + bias[i]: a sliced vector (see k_gemv) added to every row of a table
+template <typename T>
+__global__ void k_mod_add(const float* __restrict__ mtab, const float* __restrict__ e, int parts,
+                          const T* __restrict__ bias, float* __restrict__ mod, int L, int n) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < (int64_t)L * n) mod[i] = mtab[i] + e0[i % n];
+  if (i >= (int64_t)L * n) return;
+  const int c = (int)(i % n);
+  float v = bias ? Elem<T>::ld(bias + c) : 0.f;
+  for (int p = 0; p < parts; ++p) v += e[(int64_t)p * n + c];
+  mod[i] = mtab[i] + v;
 }
-void launch_mod_add(const float* mtab, const float* e0, float* mod, int L, int n, hipStream_t st) {
-  k_mod_add<<<cdiv((int64_t)L * n, 256), 256, 0, st>>>(mtab, e0, mod, L, n);
+template <typename T>
+void launch_mod_add(const float* mtab, const float* e, int parts, const T* bias, float* mod, int L, int n, hipStream_t st) {
+  k_mod_add<T><<<cdiv((int64_t)L * n, 256), 256, 0, st>>>(mtab, e, parts, bias, mod, L, n);
 }
+template void launch_mod_add<float>(const float*, const float*, int, const float*, float*, int, int, hipStream_t);
+template void launch_mod_add<bf16_t>(const float*, const float*, int, const bf16_t*, float*, int, int, hipStream_t);
 
 // cos/sin of pos * theta^(-i/pairs), angles in double
 __global__ void k_rope_table(float2* tab, int n_pos, int pairs, float theta) {

@@ -77,7 +77,7 @@ static size_t carve(dp_ends* s, void* base) {
   s->w_pe_t = take(rup(D, 256) * s->P * E);
   s->w_head_t = take(rup(s->P, 256) * D * E);
   s->tau = (float*)take(c.freq_dim * 4);
-  s->e1 = (float*)take(D * 4); s->e = (float*)take(D * 4);
+  s->e1 = (float*)take(GEMV_MAX_SLICES * D * 4); s->e = (float*)take(GEMV_MAX_SLICES * D * 4);   // sliced vectors
   s->mhead = (float*)take(2 * D * 4); s->mod = (float*)take(2 * D * 4);
   return (size_t)rup((int64_t)off, 256);
 }
@@ -156,9 +156,9 @@ static void head_typed(dp_ends* s, const void* x_in, float t, float* v_out, int 
   const dp_ends_config& c = s->cfg;
   const int64_t D = c.dim, S = s->tok * n_frames, n = S * s->P;
   launch_sinusoid(t, c.freq_dim, s->tau, st);
-  launch_gemv<T>(s->tau, c.freq_dim, (const T*)s->w.wt1, (const T*)s->w.bt1, (int)D, 0, s->e1, st);
-  launch_gemv<T>(s->e1, (int)D, (const T*)s->w.wt2, (const T*)s->w.bt2, (int)D, 1, s->e, st);
-  launch_mod_add(s->mhead, s->e, s->mod, 2, (int)D, st);                     // rows: shift, scale
+  launch_gemv<T>(s->tau, 1, 0, (const T*)nullptr, c.freq_dim, (const T*)s->w.wt1, (int)D, 0, s->e1, st);
+  launch_gemv<T>(s->e1, gemv_slices(c.freq_dim, (int)D), (int)D, (const T*)s->w.bt1, (int)D, (const T*)s->w.wt2, (int)D, 1, s->e, st);
+  launch_mod_add<T>(s->mhead, s->e, gemv_slices((int)D, (int)D), (const T*)s->w.bt2, s->mod, 2, (int)D, st);   // rows: shift, scale
   launch_to_f32<T>((const T*)x_in, s->x32, S * D, st);
   launch_ln_modulate<T>(s->x32, (T*)s->h, S, (int)D, c.eps, s->mod + D, s->mod, 1, st);
   // fp32 output through the residual epilogue (out32 += h W + b) on a cleared buffer

@@ -36,11 +36,17 @@ template <typename T>
 void launch_transpose_pad(const T* in, int64_t K, int64_t N, T* out, int64_t Npad, hipStream_t st);
 
 void launch_sinusoid(float t, int freq_dim, float* out, hipStream_t st);
-// y[n] = sum_k act(x[k]) * W[k, n] + b[n] ; act = SiLU when silu_in
+// Timestep-MLP matrix-vector product over sliced vectors.  A sliced vector is `parts` partial vectors
+// (stride apart) whose sum, plus a bias, is the value.  y receives gemv_slices(K, N) <= GEMV_MAX_SLICES partial
+// results [slice][N] of sum_k act(x[k]) * W[k, n], x[k] = sum_p x[p][k] + xbias[k]; act = SiLU when silu_in.
+constexpr int GEMV_MAX_SLICES = 8;
+int gemv_slices(int K, int N);
 template <typename T>
-void launch_gemv(const float* x, int K, const T* W, const T* b, int N, int silu_in, float* y, hipStream_t st);
-// mod[l, i] = mtab[l, i] + e0[i]
-void launch_mod_add(const float* mtab, const float* e0, float* mod, int L, int n, hipStream_t st);
+void launch_gemv(const float* x, int x_parts, int x_stride, const T* xbias, int K, const T* W, int N, int silu_in,
+                 float* y, hipStream_t st);
+// mod[l, i] = mtab[l, i] + sum_p e[p][i] + bias[i]
+template <typename T>
+void launch_mod_add(const float* mtab, const float* e, int parts, const T* bias, float* mod, int L, int n, hipStream_t st);
 void launch_rope_table(float2* tab, int n_pos, int pairs, float theta, hipStream_t st);
 void launch_fill_zero(void* p, size_t bytes, hipStream_t st);
 // dst[s, head*d + c] (fp32) = src[head][row0 + s][c]

@@ -146,8 +146,8 @@ static size_t carve(dp_stage* s, void* base) {
   const int64_t kmax = c.text_dim > D ? c.text_dim : D;
   s->wtmp = bf ? cv.take(rup(D, 256) * kmax * E) : nullptr;
   s->tau = (float*)cv.take(c.freq_dim * 4);
-  s->e1 = (float*)cv.take(D * 4); s->e2 = (float*)cv.take(D * 4);
-  s->e0 = (float*)cv.take(6 * D * 4);
+  s->e1 = (float*)cv.take(GEMV_MAX_SLICES * D * 4); s->e2 = (float*)cv.take(GEMV_MAX_SLICES * D * 4);   // sliced vectors
+  s->e0 = (float*)cv.take(GEMV_MAX_SLICES * 6 * D * 4);
   s->mtab = (float*)cv.take(L * 6 * D * 4);
   s->mod = (float*)cv.take(L * 6 * D * 4);
   const int half = c.head_dim / 2, c_sp = c.head_dim / 6, c_f = half - 2 * c_sp;
@@ -334,10 +334,10 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
   // adaLN modulation: sinusoidal features -> two-layer MLP (SiLU) -> SiLU -> 6*dim head, plus each layer's table
   PROF(DP_PROF_MODULATION,
        launch_sinusoid(t, c.freq_dim, s->tau, st);
-       launch_gemv<T>(s->tau, c.freq_dim, (const T*)s->w.wt1, (const T*)s->w.bt1, (int)D, 0, s->e1, st);
-       launch_gemv<T>(s->e1, (int)D, (const T*)s->w.wt2, (const T*)s->w.bt2, (int)D, 1, s->e2, st);
-       launch_gemv<T>(s->e2, (int)D, (const T*)s->w.wm, (const T*)s->w.bm, (int)(6 * D), 1, s->e0, st);
-       launch_mod_add(s->mtab, s->e0, s->mod, c.n_layers, (int)(6 * D), st));
+       launch_gemv<T>(s->tau, 1, 0, (const T*)nullptr, c.freq_dim, (const T*)s->w.wt1, (int)D, 0, s->e1, st);
+       launch_gemv<T>(s->e1, gemv_slices(c.freq_dim, (int)D), (int)D, (const T*)s->w.bt1, (int)D, (const T*)s->w.wt2, (int)D, 1, s->e2, st);
+       launch_gemv<T>(s->e2, gemv_slices((int)D, (int)D), (int)D, (const T*)s->w.bt2, (int)D, (const T*)s->w.wm, (int)(6 * D), 1, s->e0, st);
+       launch_mod_add<T>(s->mtab, s->e0, gemv_slices((int)D, (int)(6 * D)), (const T*)s->w.bm, s->mod, c.n_layers, (int)(6 * D), st));
   const int64_t kv_hs = s->Lpad * d;        // head stride of kbuf
   // where this block's keys go: directly before the cached range if it fits there, else directly after it
   // (the buffer holds 2 * Smax + Ncmax positions, so one side always has room)
