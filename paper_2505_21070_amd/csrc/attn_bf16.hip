@@ -401,11 +401,8 @@ static void launch_attn_cfg(const bf16_t* q, int64_t q_head_stride, const bf16_t
     if (parts < 1) parts = 1;
   }
   dim3 grid((unsigned)(n_full + (n_tail * parts + 7) / 8 * 8));
-  static bool attr_done = false;
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_attn_bf16<HD, QG, KG>, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    attr_done = true;
-  }
+  static std::atomic<uint64_t> done;
+  allow_dynamic_lds((const void*)k_attn_bf16<HD, QG, KG>, lds, done);
   k_attn_bf16<HD, QG, KG><<<grid, 512, lds, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch);
   if (parts > 1) {
     constexpr int QPB = 256 / (HD / 4);                  // queries per merge block

@@ -264,24 +264,20 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool RESID_OK = true>
+template <int BM, int BN, int WGM, int WGN>
 static void launch_cfg(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
                        int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
   constexpr int NT = WGM * WGN * 64;
   constexpr size_t lds = (size_t)(BM + BN) * 128 * 2;
   const int tm = (int)((M + BM - 1) / BM), tn = (int)((N + BN - 1) / BN);
-  static bool attr_done = false;
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_STORE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    (void)hipFuncSetAttribute((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_GELU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if constexpr (RESID_OK)
-      (void)hipFuncSetAttribute((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_done = true;
-  }
+  static std::atomic<uint64_t> done[3];
+  if (epi == EPI_STORE) allow_dynamic_lds((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_STORE>, (int)lds, done[0]);
+  else if (epi == EPI_GELU) allow_dynamic_lds((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_GELU>, (int)lds, done[1]);
+  else allow_dynamic_lds((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID>, (int)lds, done[2]);
   dim3 grid((unsigned)((tm * tn + 7) / 8 * 8));
   if (epi == EPI_STORE) k_gemm_bf16<BM, BN, WGM, WGN, EPI_STORE><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
   else if (epi == EPI_GELU) k_gemm_bf16<BM, BN, WGM, WGN, EPI_GELU><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
-  else if constexpr (RESID_OK) k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
+  else k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
 }
 
 void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,

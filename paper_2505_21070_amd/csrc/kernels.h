@@ -1,5 +1,6 @@
 // Host-side launchers of libdualparal's kernels.  Every launcher only enqueues work on `st`.
 #pragma once
+#include <atomic>
 #include "common.h"
 
 // ---- elementwise.hip -------------------------------------------------------------------------
@@ -71,6 +72,17 @@ void launch_attn_f32(const float* q, int64_t q_head_stride, const float* k, int6
 // out[f, :] = pool[index[f], :], frame_bytes % 16 == 0, all pointers 16-byte aligned
 void launch_gather_frames(const void* pool, int pool_frames, int64_t frame_bytes, const int32_t* index,
                           int n_frames, void* out, hipStream_t st);
+// Raises a kernel's dynamic-LDS limit once per device and process (the attribute belongs to the device's copy
+// of the code object).  `done` is one bit per device ordinal; safe to call from several host threads.
+inline void allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return;
+  (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  done.fetch_or(bit, std::memory_order_release);
+}
+
 // ---- gemm_bf16.hip : C = A[M,K] * Wt[N,K]^T (+ epilogue), bf16 MFMA, fp32 accumulate --------
 // A must be readable for roundup(M, 256) rows, Wt for roundup(N, 256) rows; K % 64 == 0.
 void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M,
