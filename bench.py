@@ -196,12 +196,81 @@ def latent_step(args):
                       "parts": parts}))
 
 
+def long_sweep(args):
+    """Informational: the long-video configuration end to end in latent space on one GPU that holds all 30 layers:
+    257 latent frames as one 5-frame block + 63 blocks of 4 (the first block is the longer one, Sec. 3.3), T noise
+    levels, the whole block queue from the first push to the last pop (T * 64 block passes).  Every pass is
+    patch embedding -> 30 layers with the neighbour's cached K/V -> cache hand-over -> output head -> Euler
+    update of the block's latent frames.  Reports sustained tokens/s over the whole run and peak device memory."""
+    from paper_2505_21070_amd import binding as B
+    from paper_2505_21070_amd import synth
+    torch.cuda.set_device(0)
+    C, frames, nf, nc, first, block_num, T = 16, 257, 4, 2, 5, 64, args.levels
+    cfg, weights, text, _ = synth.make_case("wan1p3b_full", seed=0, n_blocks=0)
+    tok, td = cfg["tok_h"] * cfg["tok_w"], torch.bfloat16
+    torch.cuda.reset_peak_memory_stats()
+    free0, _total = torch.cuda.mem_get_info()
+    stage = B.Stage(B.make_config(cfg, max_block_frames=first, max_cache_frames=nc, max_abs_frames=frames + 7),
+                    B.weights_to_device(weights, cfg["dtype"]), text.to("cuda", td).contiguous())
+    dev = {k: v.to("cuda", td).contiguous() for k, v in synth.make_end_weights(cfg, C, 0).items()}
+    dev.update({k: weights["stage"][k].to("cuda", td).contiguous() for k in ("wt1", "bt1", "wt2", "bt2")})
+    ends = B.Ends(cfg, dev, C, first)
+    # coordinated noise initialisation: every block's frames come from one pool of num_b + num_c/2 noise frames;
+    # block 1 is one frame shorter here than the pool (257 = 5 + 63 * 4), so it takes the pool's last 5 frames
+    gen = torch.Generator().manual_seed(1)
+    pool = synth.make_latent(cfg, nf + nc, C, gen).cuda()
+    idx = B.noise_assign(block_num, nf, 2 * nc, synth.shuffle_words((block_num - 1) * (nf - 1), 2))
+    idx[0] = idx[0][-first:]
+    flat = torch.tensor([i for blk in idx for i in blk], dtype=torch.int32, device="cuda")
+    assert flat.numel() == frames
+    sched = B.blockwise_schedule(T, block_num, nf, 2 * nc, first, 1000.0, "reverse")
+    assert len(sched) == T * block_num and sched[-1]["frame0"] + sched[-1]["n_frames"] <= frames
+    assert max(e["frame0"] + e["n_frames"] for e in sched) == frames
+    out = torch.empty((first * tok, cfg["dim"]), dtype=td, device="cuda")
+
+    def run():
+        lat = B.noise_gather(pool, flat)                  # [257, 60, 104, 16] fp32, the video's latent frames
+        for e in sched:
+            n, f0, k = e["n_frames"], e["frame0"], e["level"]
+            if e["cache_block"] == 0:
+                stage.cache_update(0, 0)
+            blk = lat[f0:f0 + n]
+            y = out[:n * tok]
+            stage.forward(ends.embed(blk), n, f0, e["timestep"], out=y)
+            stage.cache_update(0, nc)
+            B.euler_step(blk, ends.head(y, e["timestep"], n), k / T, (k - 1) / T)
+        return lat
+
+    for e in sched[:2]:                                   # warm-up: two passes
+        stage.forward(ends.embed(pool[:e["n_frames"]].contiguous()), e["n_frames"], e["frame0"], e["timestep"])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    lat = run()
+    torch.cuda.synchronize()
+    sec = time.perf_counter() - t0
+    assert torch.isfinite(lat).all()
+    free1, _ = torch.cuda.mem_get_info()
+    tokens = sum(e["n_frames"] for e in sched) * tok
+    print(json.dumps({"metric": "latent tokens/sec per DiT stage (cached block); attn+FFN TFLOP/s vs bf16 MFMA peak",
+                      "value": tokens / sec, "unit": "tokens/s", "n_gpus": 1, "steps": len(sched), "warmup": 2,
+                      "ms_per_step": sec * 1e3 / len(sched), "higher_is_better": True, "scaling": "weak",
+                      "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": f"wan1p3b_long (informational: 257 latent frames, 64 blocks, T = {T} levels, "
+                                             "30 layers + both ends + Euler in latent space; one step = one block pass)",
+                                 "layers": cfg["n_layers"], "latent_frames": frames, "blocks": block_num, "levels": T,
+                                 "block_passes": len(sched), "tokens_processed": tokens},
+                      "run_seconds": sec,
+                      "peak_hbm_bytes": {"torch_max_allocated": torch.cuda.max_memory_allocated(),
+                                         "device_in_use_delta": free0 - free1}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="wan1p3b_stage")
+    ap.add_argument("--levels", type=int, default=8, help="noise levels T of the wan1p3b_long workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-class time table to stderr")
     args = ap.parse_args()
@@ -215,6 +284,8 @@ def main():
         return cache_ablation(args)
     if args.workload == "wan1p3b_latent":
         return latent_step(args)
+    if args.workload == "wan1p3b_long":
+        return long_sweep(args)
     from paper_2505_21070_amd import binding as B
     from paper_2505_21070_amd import synth
 
