@@ -267,7 +267,9 @@ void dp_ends_free(dp_ends_t* ends);
  *   dst  : device float buffer of at least `capacity` floats; *rows receives the row count.
  * Errors: DP_ESTATE, DP_EINVAL, DP_ENOMEM. */
 enum { DP_PEEK_K = 0, DP_PEEK_V = 1, DP_PEEK_CACHE_K = 2, DP_PEEK_CACHE_V = 3,
-       DP_PEEK_Q = 4 /* cross-attention queries of the last layer; DP_BF16: times log2(e)/sqrt(head_dim) */,
+       DP_PEEK_Q = 4 /* cross-attention queries of the last layer as the attention kernel uses them; DP_BF16: times
+                        log2(e)/sqrt(head_dim), and with dim % 256 == 0 without their RMSNorm gains, which then sit
+                        in DP_PEEK_TEXT_K instead */,
        DP_PEEK_ATTN = 5, DP_PEEK_CROSS_ATTN = 6, DP_PEEK_X_SELF = 7, DP_PEEK_X_CROSS = 8,
        DP_PEEK_MOD = 9 /* [6, dim] of `layer` */, DP_PEEK_TEXT_K = 10, DP_PEEK_TEXT_V = 11,
        DP_PEEK_X_RES = 12 /* the fp32 residual stream after the last layer, before rounding to x_out */ };

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
                                                   int64_t vt_row_stride, int64_t S, int64_t L,
                                                   bf16_t* __restrict__ out, int64_t ldo, int qblocks,
                                                   int n_full, int n_tail, int parts,
-                                                  float* __restrict__ partial) {
+                                                  float* __restrict__ partial, AttnQNorm qn) {
   constexpr int CR = HD / 8;                 // 16-byte chunks per K row
   constexpr int KS = HD / 16;                // MFMA k-steps over the head dim
   constexpr int DT = HD / 32;                // 32-row tiles of O^T
@@ -115,6 +115,21 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
     const bf16_t* qh = q + (int64_t)head * q_head_stride + (q0 + lr) * HD + lg * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *(const uint4*)(qh + ks * 16));
+  }
+  if (qn.ssq) {
+    // deferred RMSNorm of the queries: the row's sum of squares arrives as qn.np partial sums; the two lanes
+    // that share a query row add up the even and the odd ones
+    const int64_t row = q0 + lr < S ? q0 + lr : S - 1;
+    const float* pr = qn.ssq + row;
+    float sum = 0.f;
+#pragma unroll 4
+    for (int i = lg; i < qn.np; i += 2) sum += pr[i * qn.stride];
+    sum += __shfl_xor(sum, 32, 64);
+    const float r = rsqrtf(sum * qn.inv_dim + qn.eps) * qn.scale;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[ks][e] = (__bf16)((float)qf[ks][e] * r);
   }
   const bf16_t* kh = k + (int64_t)head * k_head_stride + (k_row0 + (int64_t)first * 64) * HD;
   const bf16_t* vh = vt + (int64_t)head * HD * vt_row_stride + k_row0 + (int64_t)first * 64;
@@ -384,7 +399,7 @@ size_t attn_bf16_scratch_bytes(int d) { return (size_t)256 * (512 + 256 * (size_
 template <int HD, int QG, int KG>
 static void launch_attn_cfg(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
                             int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
-                            int h, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st) {
+                            int h, bf16_t* out, int64_t ldo, float* scratch, const AttnQNorm& qn, hipStream_t st) {
   constexpr int QB = QG * 32;
   constexpr int lds = KG * 2 * (64 * (HD / 8) + HD * 8) * 16;
   const int qblocks = (int)((S + QB - 1) / QB);
@@ -403,7 +418,7 @@ static void launch_attn_cfg(const bf16_t* q, int64_t q_head_stride, const bf16_t
   dim3 grid((unsigned)(n_full + (n_tail * parts + 7) / 8 * 8));
   static std::atomic<uint64_t> done;
   allow_dynamic_lds((const void*)k_attn_bf16<HD, QG, KG>, lds, done);
-  k_attn_bf16<HD, QG, KG><<<grid, 512, lds, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch);
+  k_attn_bf16<HD, QG, KG><<<grid, 512, lds, st>>>(q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, out, ldo, qblocks, n_full, n_tail, parts, scratch, qn);
   if (parts > 1) {
     constexpr int QPB = 256 / (HD / 4);                  // queries per merge block
     k_attn_merge<HD, QB><<<(unsigned)(n_tail * (QB / QPB)), 256, 0, st>>>(scratch, n_full, n_tail, parts, qblocks, S, out, ldo);
@@ -412,13 +427,14 @@ static void launch_attn_cfg(const bf16_t* q, int64_t q_head_stride, const bf16_t
 
 void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
                       int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
-                      int h, int d, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st) {
+                      int h, int d, bf16_t* out, int64_t ldo, float* scratch, const AttnQNorm* qnorm, hipStream_t st) {
   if (S <= 0 || L <= 0) return;
+  const AttnQNorm qn = qnorm ? *qnorm : AttnQNorm{nullptr, 0, 0, 0.f, 0.f, 0.f};
   // 256 queries per block share every K / V^T tile (half the LDS fill traffic per query) whenever that
   // still gives the grid half a round of blocks and the key range a few tiles; otherwise 128 queries per
   // block with the keys split over two groups, which halves the length of a block.
   const bool wide = L >= 256 && ((S + 255) / 256) * h >= 128;
-#define ATTN_ARGS q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, h, out, ldo, scratch, st
+#define ATTN_ARGS q, q_head_stride, k, k_head_stride, k_row0, vt, vt_row_stride, S, L, h, out, ldo, scratch, qn, st
   if (d == 128) { if (wide) launch_attn_cfg<128, 8, 1>(ATTN_ARGS); else launch_attn_cfg<128, 4, 2>(ATTN_ARGS); }
   else { if (wide) launch_attn_cfg<64, 8, 1>(ATTN_ARGS); else launch_attn_cfg<64, 4, 2>(ATTN_ARGS); }
 #undef ATTN_ARGS

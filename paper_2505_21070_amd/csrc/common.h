@@ -53,8 +53,34 @@ __device__ __forceinline__ float gelu_tanh_f(float v) {
 }
 __device__ __forceinline__ float silu_f(float v) { return v / (1.0f + __expf(-v)); }
 
-// GEMM epilogue selector (shared by the fp32 and the bf16 GEMM kernels)
-enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2 };
+// GEMM epilogue selector (shared by the fp32 and the bf16 GEMM kernels; EPI_HEADS is bf16 only)
+enum { EPI_STORE = 0, EPI_GELU = 1, EPI_RESID = 2, EPI_HEADS = 3 };
+
+struct RopeTables {            // cos/sin pairs: tab[pos][pair] = (cos, sin)
+  const float2* f; const float2* y; const float2* x;
+  int c_f, c_h, c_w;           // pairs per axis
+};
+
+// EPI_HEADS: the output columns are up to three sections of `dim` columns each (e.g. q | k | v of a fused
+// projection); a section is written per attention head instead of row-major.
+struct HeadSection {
+  void* dst;               // plain: [dim / head_dim][..][head_dim], element (head, row0 + m, c);
+                           // transposed: [dim][ld], element (channel, row0 + m)
+  int64_t ld;              // plain: elements between heads; transposed: elements between channels
+  int64_t row0;            // first destination row (transposed: column) of output row m = 0
+  const float* gain;       // fp32 [dim] multiplied in before the rotation, or null
+  float* ssq;              // fp32 [ssq_np][ssq_stride]: element (t, m) = sum of squares of row m's (acc + bias) over
+                           // the t-th run of dim / ssq_np columns of the section (one run per block tile), or null
+  int rope;                // rotate channel pairs (2i, 2i+1) of each head by the row's entries of HeadsArgs::cs
+  int transposed;          // written channel-major; such tiles are computed with the operands exchanged
+};
+struct HeadsArgs {
+  HeadSection sec[3];
+  int dim, head_dim;       // section width, head width
+  int64_t ssq_stride;      // >= M
+  int ssq_np;              // out: partial sums per row and section that the chosen tile shape produces
+  const float2* cs;        // [M][head_dim / 2] (cos, sin) of output row m and channel pair i, for sections with rope
+};
 
 struct EpiArgs {
   void* out;            // EPI_STORE / EPI_GELU: [M, ldo] of the activation type
@@ -63,4 +89,5 @@ struct EpiArgs {
   float* resid;         // EPI_RESID: fp32 [M, ldr], updated in place: resid += gate * (acc + bias)
   int64_t ldr;
   const float* gate;    // EPI_RESID: fp32 [N] or null (= 1)
+  HeadsArgs* heads;        // EPI_HEADS: host pointer, copied into the launch; its ssq_np is filled in
 };

@@ -32,6 +32,14 @@ template void launch_to_f32<bf16_t>(const bf16_t*, float*, int64_t, hipStream_t)
 template void launch_from_f32<float>(const float*, float*, int64_t, hipStream_t);
 template void launch_from_f32<bf16_t>(const float*, bf16_t*, int64_t, hipStream_t);
 
+__global__ void k_mul_f32(const float* __restrict__ a, const float* __restrict__ b, float* __restrict__ out, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = a[i] * b[i];
+}
+void launch_mul_f32(const float* a, const float* b, float* out, int64_t n, hipStream_t st) {
+  if (n > 0) k_mul_f32<<<cdiv(n, 256), 256, 0, st>>>(a, b, out, n);
+}
+
 __global__ void k_fill_zero(uint32_t* p, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -110,41 +118,46 @@ template void launch_ln_modulate<float>(const float*, float*, int64_t, int, floa
 template void launch_ln_modulate<bf16_t>(const float*, bf16_t*, int64_t, int, float, const float*, const float*, int, hipStream_t);
 
 // ---------------------------------------------------------------- RMSNorm over D + 3D RoPE, head-major output
-// One block per token and job (blockIdx.y: e.g. q and k of the same row).  A thread owns groups of 8
-// consecutive channels (one 16-byte access for bf16), kept in registers between the sum-of-squares
-// pass and the normalise/rotate/store pass, so the row is read once.
+// One wavefront per token and job (blockIdx.y: e.g. q and k of the same row), four tokens per block.  A lane
+// owns VPL groups of 8 consecutive channels (one 16-byte access each for bf16), all loaded before the first
+// use so that a wavefront keeps VPL KiB in flight, and kept in registers between the sum-of-squares pass and
+// the normalise/rotate/store pass: the row is read once, and nothing but wavefront shuffles synchronises.
 template <typename T> struct alignas(sizeof(T) * 8) Vec8 { T v[8]; };
 
-template <typename T>
-__global__ __launch_bounds__(256) void k_norm_rope(const T* __restrict__ src, int64_t ld, int h, int d, float eps,
-                                                   NormRopeJob<T> j0, NormRopeJob<T> j1, int64_t row0,
+template <typename T, int VPL>
+__global__ __launch_bounds__(256) void k_norm_rope(const T* __restrict__ src, int64_t ld, int64_t S, int h, int d,
+                                                   float eps, NormRopeJob<T> j0, NormRopeJob<T> j1,
                                                    RopeTables rt, int frame0, int tok_h, int tok_w) {
-  __shared__ float red[4];
   const NormRopeJob<T> job = blockIdx.y == 0 ? j0 : j1;
-  const int64_t s = blockIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (s >= S) return;
   const int D = h * d, nvec = D >> 3;
   const Vec8<T>* row = (const Vec8<T>*)(src + s * ld + job.col);
-  float v[4][8];
+  Vec8<T> raw[VPL];
+#pragma unroll
+  for (int i = 0; i < VPL; ++i) {
+    const int vi = lane + i * 64;
+    if (vi < nvec) raw[i] = row[vi];
+  }
+  float v[VPL][8];
   float sq = 0.f;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int vi = threadIdx.x + i * 256;
-    if (vi < nvec) {
-      const Vec8<T> t = row[vi];
+  for (int i = 0; i < VPL; ++i) {
+    const int vi = lane + i * 64;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { v[i][e] = Elem<T>::ld(&t.v[e]); sq += v[i][e] * v[i][e]; }
+    for (int e = 0; e < 8; ++e) {
+      v[i][e] = vi < nvec ? Elem<T>::ld(&raw[i].v[e]) : 0.f;
+      sq += v[i][e] * v[i][e];
     }
   }
-  sq = wave_sum(sq);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sq;
-  __syncthreads();
-  const float r = rsqrtf(((red[0] + red[1]) + (red[2] + red[3])) / (float)D + eps) * job.out_scale;
+  const float r = rsqrtf(wave_sum(sq) / (float)D + eps) * job.out_scale;
   const int tok = tok_h * tok_w;
   const int f = frame0 + (int)(s / tok), rem = (int)(s % tok);
   const int y = rem / tok_w, x = rem % tok_w;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int vi = threadIdx.x + i * 256;
+  for (int i = 0; i < VPL; ++i) {
+    const int vi = lane + i * 64;
     if (vi < nvec) {
       const int c0 = vi * 8, head = c0 / d, p0 = (c0 % d) >> 1;        // first channel, its head, first pair in the head
       const float4 g0 = *(const float4*)(job.g + c0), g1 = *(const float4*)(job.g + c0 + 4);
@@ -176,11 +189,87 @@ void launch_norm_rope(const T* src, int64_t ld, int64_t S, int h, int d, float e
   RopeTables rt = rope ? *rope : RopeTables{nullptr, nullptr, nullptr, 0, 0, 0};
   NormRopeJob<T> j0 = jobs[0], j1 = jobs[n_jobs > 1 ? 1 : 0];
   if (!rope) { j0.rope = 0; j1.rope = 0; }
-  k_norm_rope<T><<<dim3((unsigned)S, (unsigned)(n_jobs > 1 ? 2 : 1)), 256, 0, st>>>(
-      src, ld, h, d, eps, j0, j1, 0, rt, frame0, tok_h > 0 ? tok_h : 1, tok_w > 0 ? tok_w : 1);
+  const dim3 grid((unsigned)cdiv(S, 4), (unsigned)(n_jobs > 1 ? 2 : 1));
+  const int th = tok_h > 0 ? tok_h : 1, tw = tok_w > 0 ? tok_w : 1;
+  const int vpl = (h * d / 8 + 63) / 64;               // 16-byte groups per lane; dim <= 8192
+#define NORM_ROPE_CASE(V) k_norm_rope<T, V><<<grid, 256, 0, st>>>(src, ld, S, h, d, eps, j0, j1, rt, frame0, th, tw)
+  if (vpl <= 1) NORM_ROPE_CASE(1);
+  else if (vpl <= 3) NORM_ROPE_CASE(3);
+  else if (vpl <= 6) NORM_ROPE_CASE(6);
+  else if (vpl <= 10) NORM_ROPE_CASE(10);
+  else NORM_ROPE_CASE(16);
+#undef NORM_ROPE_CASE
 }
 template void launch_norm_rope<float>(const float*, int64_t, int64_t, int, int, float, const NormRopeJob<float>*, int, const RopeTables*, int, int, int, hipStream_t);
 template void launch_norm_rope<bf16_t>(const bf16_t*, int64_t, int64_t, int, int, float, const NormRopeJob<bf16_t>*, int, const RopeTables*, int, int, int, hipStream_t);
+
+// ---------------------------------------------------------------- per-token rotation table of one block
+// cs[s][i] = (cos, sin) of channel pair i at token s = (frame0 + s / (tok_h * tok_w), y, x), gathered from the
+// three per-axis tables
+__global__ void k_rope_tokens(RopeTables rt, int frame0, int tok_h, int tok_w, int64_t S, float2* __restrict__ cs) {
+  const int half = rt.c_f + rt.c_h + rt.c_w;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= S * half) return;
+  const int64_t s = i / half; const int pi = (int)(i % half);
+  const int tok = tok_h * tok_w, rem = (int)(s % tok);
+  const int f = frame0 + (int)(s / tok), y = rem / tok_w, x = rem % tok_w;
+  float2 v;
+  if (pi < rt.c_f) v = rt.f[(int64_t)f * rt.c_f + pi];
+  else if (pi < rt.c_f + rt.c_h) v = rt.y[y * rt.c_h + (pi - rt.c_f)];
+  else v = rt.x[x * rt.c_w + (pi - rt.c_f - rt.c_h)];
+  cs[i] = v;
+}
+void launch_rope_tokens(const RopeTables& rt, int frame0, int tok_h, int tok_w, int64_t S, float2* cs, hipStream_t st) {
+  if (S <= 0) return;
+  k_rope_tokens<<<cdiv(S * (rt.c_f + rt.c_h + rt.c_w), 256), 256, 0, st>>>(rt, frame0, tok_h, tok_w, S, cs);
+}
+
+// ---------------------------------------------------------------- deferred RMSNorm of head-major bf16 rows
+// k[head][row0 + s][:] *= rsqrt(sum_i ssq[i * stride + s] * inv_dim + eps) for every head: the row scale of an
+// RMSNorm whose gains and rotation a GEMM epilogue has applied already.  One wavefront per token.
+template <int VPL>
+__global__ __launch_bounds__(256) void k_scale_rows(bf16_t* __restrict__ k, int64_t head_stride, int64_t row0, int64_t S,
+                                                    int h, int d, const float* __restrict__ ssq, int np,
+                                                    int64_t stride, float inv_dim, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (s >= S) return;
+  const int nvec = (h * d) >> 3;
+  uint4 raw[VPL];
+#pragma unroll
+  for (int i = 0; i < VPL; ++i) {
+    const int c0 = (lane + i * 64) * 8;
+    if (lane + i * 64 < nvec) raw[i] = *(const uint4*)(k + (int64_t)(c0 / d) * head_stride + (row0 + s) * d + c0 % d);
+  }
+  float sum = 0.f;
+  for (int i = lane; i < np; i += 64) sum += ssq[i * stride + s];
+  const float r = rsqrtf(wave_sum(sum) * inv_dim + eps);
+#pragma unroll
+  for (int i = 0; i < VPL; ++i) {
+    const int c0 = (lane + i * 64) * 8;
+    if (lane + i * 64 < nvec) {
+      const uint32_t w[4] = {raw[i].x, raw[i].y, raw[i].z, raw[i].w};
+      uint32_t o[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        o[e] = pack_bf16x2(bf16_to_f32((bf16_t)(w[e] & 0xffff)) * r, bf16_to_f32((bf16_t)(w[e] >> 16)) * r);
+      *(uint4*)(k + (int64_t)(c0 / d) * head_stride + (row0 + s) * d + c0 % d) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+  }
+}
+void launch_scale_rows_bf16(bf16_t* k, int64_t head_stride, int64_t row0, int64_t S, int h, int d, const float* ssq,
+                            int np, int64_t stride, float eps, hipStream_t st) {
+  if (S <= 0) return;
+  const int vpl = (h * d / 8 + 63) / 64;
+  const float inv_dim = 1.f / (float)(h * d);
+#define SCALE_ROWS_CASE(V) k_scale_rows<V><<<cdiv(S, 4), 256, 0, st>>>(k, head_stride, row0, S, h, d, ssq, np, stride, inv_dim, eps)
+  if (vpl <= 1) SCALE_ROWS_CASE(1);
+  else if (vpl <= 3) SCALE_ROWS_CASE(3);
+  else if (vpl <= 6) SCALE_ROWS_CASE(6);
+  else if (vpl <= 10) SCALE_ROWS_CASE(10);
+  else SCALE_ROWS_CASE(16);
+#undef SCALE_ROWS_CASE
+}
 
 // ---------------------------------------------------------------- V -> V^T (per head [d][L])
 // 64 tokens x 64 channels through LDS: 16-byte reads along channels, 16-byte writes along tokens.
@@ -408,6 +497,24 @@ void launch_gather_heads(const T* src, int64_t head_stride, int64_t row0, int64_
                          float* dst, hipStream_t st) {
   if (S <= 0) return;
   k_gather_heads<T><<<cdiv(S * h * d, 256), 256, 0, st>>>(src, head_stride, row0, S, h, d, dst);
+}
+// the queries as the bf16 attention kernel uses them when their RMSNorm is deferred: same sums, same rounding
+__global__ void k_gather_heads_qnorm(const bf16_t* __restrict__ src, int64_t head_stride, int64_t S, int h, int d,
+                                     AttnQNorm qn, float* __restrict__ dst) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int D = h * d;
+  if (i >= S * D) return;
+  const int64_t s = i / D; const int c = (int)(i % D);
+  float even = 0.f, odd = 0.f;
+  for (int j = 0; j < qn.np; j += 2) even += qn.ssq[j * qn.stride + s];
+  for (int j = 1; j < qn.np; j += 2) odd += qn.ssq[j * qn.stride + s];
+  const float r = rsqrtf((even + odd) * qn.inv_dim + qn.eps) * qn.scale;
+  dst[i] = bf16_to_f32(f32_to_bf16(bf16_to_f32(src[(int64_t)(c / d) * head_stride + s * d + (c % d)]) * r));
+}
+void launch_gather_heads_qnorm(const bf16_t* src, int64_t head_stride, int64_t S, int h, int d, const AttnQNorm& qn,
+                               float* dst, hipStream_t st) {
+  if (S <= 0) return;
+  k_gather_heads_qnorm<<<cdiv(S * h * d, 256), 256, 0, st>>>(src, head_stride, S, h, d, qn, dst);
 }
 template void launch_gather_heads<float>(const float*, int64_t, int64_t, int64_t, int, int, float*, hipStream_t);
 template void launch_gather_heads<bf16_t>(const bf16_t*, int64_t, int64_t, int64_t, int, int, float*, hipStream_t);

@@ -34,7 +34,7 @@ template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A, int64_t lda,
                                                              const bf16_t* __restrict__ Bt, int64_t ldb,
                                                              int64_t M, int64_t N, int64_t K, int tiles_n,
-                                                             int tiles, EpiArgs e) {
+                                                             int tiles, EpiArgs e, HeadsArgs ha) {
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -61,18 +61,29 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   const int64_t m0 = (int64_t)(band * 4 + in_band % band_rows) * BM, n0 = (int64_t)(in_band / band_rows) * BN;
   const int KT = (int)(K / 64);
 
+  // EPI_HEADS: a tile of a section that is stored channel-major is computed with the operands exchanged
+  // (square tiles only), so that its accumulators, staging tile and row stores are those of C^T
+  int sec = 0;
+  bool swapped = false;
+  if constexpr (EPI == EPI_HEADS) {
+    sec = (int)(n0 / ha.dim);
+    if constexpr (BM == BN) swapped = ha.sec[sec].transposed != 0;
+  }
+  const bf16_t* const pa = swapped ? Bt + n0 * ldb : A + m0 * lda;
+  const bf16_t* const pb = swapped ? A + m0 * lda : Bt + n0 * ldb;
+  const int64_t lpa = swapped ? ldb : lda, lpb = swapped ? lda : ldb;
   // slot p of a tile holds chunk (p & 7) ^ ((row >> 1) & 7) of row p >> 3; one wavefront instruction
   // fills slots [base, base + 64), lane l the slot base + l
   const bf16_t* gA[IA]; const bf16_t* gB[IB];
 #pragma unroll
   for (int i = 0; i < IA; ++i) {
     const int p = (wave * IA + i) * 64 + lane, row = p >> 3, ch = (p & 7) ^ ((row >> 1) & 7);
-    gA[i] = A + (m0 + row) * lda + ch * 8;
+    gA[i] = pa + row * lpa + ch * 8;
   }
 #pragma unroll
   for (int i = 0; i < IB; ++i) {
     const int p = (wave * IB + i) * 64 + lane, row = p >> 3, ch = (p & 7) ^ ((row >> 1) & 7);
-    gB[i] = Bt + (n0 + row) * ldb + ch * 8;
+    gB[i] = pb + row * lpb + ch * 8;
   }
   auto load_tile = [&](int kt, int bufi) __attribute__((always_inline)) {
     if (kt >= KT) return;
@@ -154,7 +165,168 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   // neither the column-wise writes nor the row-wise reads conflict on banks.
   constexpr int NW = WGM * WGN;
   const bf16_t* bias = (const bf16_t*)e.bias;
-  if constexpr (EPI != EPI_RESID) {
+  if constexpr (EPI == EPI_HEADS) {
+    // Sections of `dim` columns, each stored per attention head (see HeadsArgs).  A plain section gets, per
+    // output row, the sum of squares of (acc + bias) over this tile's columns, taken from the fp32
+    // accumulators; its channel gains and 3D rotation are applied on the way out of the staging tile, where
+    // a lane holds 8 consecutive channels of one row, so that the table and gain reads are contiguous
+    // across lanes.  A transposed section is C^T already.
+    constexpr int UPR = BN / 4, CPR = BN / 8, RPI = 64 / CPR;
+    static_assert(BM * BN * 2 <= (BM + BN) * 256, "EPI_HEADS stages the whole tile at once");
+    __shared__ float red[BM * WGN];                      // [row][wavefront column]: sums of squares
+    const HeadSection sc = ha.sec[sec];
+    const int64_t nsec = n0 - (int64_t)sec * ha.dim;     // first column of this tile inside its section
+    const int hshift = ha.head_dim == 128 ? 7 : 6, hmask = ha.head_dim - 1;
+    uint2* l8 = (uint2*)smem;
+    __syncthreads();
+    if (swapped) {
+      // lane: channel row (weight row) nsec + wm*WM + i*32 + lr; register quad: 4 consecutive output rows m
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = wm * WM + i * 32 + lr;
+        const float bvr = bias && n0 + row < N ? bf16_to_f32(bias[n0 + row]) : 0.f;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int nl = wn * WN + j * 32 + q * 8 + lg * 4;
+            uint2 pk;
+            pk.x = cvt_pk_bf16(acc[i][j][q * 4 + 0] + bvr, acc[i][j][q * 4 + 1] + bvr);
+            pk.y = cvt_pk_bf16(acc[i][j][q * 4 + 2] + bvr, acc[i][j][q * 4 + 3] + bvr);
+            l8[row * UPR + ((nl >> 2) ^ (row & 31))] = pk;
+          }
+      }
+    } else {
+      float ss[TM];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) ss[i] = 0.f;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int nl = wn * WN + j * 32 + q * 8 + lg * 4;
+          float bv[4] = {0.f, 0.f, 0.f, 0.f};
+          if (bias && n0 + nl < N) {
+            const uint2 b4 = *(const uint2*)(bias + n0 + nl);
+            bv[0] = bf16_to_f32((bf16_t)(b4.x & 0xffff)); bv[1] = bf16_to_f32((bf16_t)(b4.x >> 16));
+            bv[2] = bf16_to_f32((bf16_t)(b4.y & 0xffff)); bv[3] = bf16_to_f32((bf16_t)(b4.y >> 16));
+          }
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            const int row = wm * WM + i * 32 + lr;
+            float v[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              v[t] = acc[i][j][q * 4 + t] + bv[t];
+              ss[i] += v[t] * v[t];
+            }
+            uint2 pk;
+            pk.x = cvt_pk_bf16(v[0], v[1]);
+            pk.y = cvt_pk_bf16(v[2], v[3]);
+            l8[row * UPR + ((nl >> 2) ^ (row & 31))] = pk;
+          }
+        }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const float tot = ss[i] + __shfl_xor(ss[i], 32, 64);
+        if (lg == 0) red[(wm * WM + i * 32 + lr) * WGN + wn] = tot;
+      }
+    }
+    __syncthreads();
+    if (!swapped && sc.ssq) {
+      // one value per row and tile, tile-major so that rows are contiguous: ssq[tile in section][m]
+      for (int row = tid; row < BM; row += NT) {
+        float tot = 0.f;
+#pragma unroll
+        for (int w = 0; w < WGN; ++w) tot += red[row * WGN + w];
+        if (m0 + row < M) sc.ssq[(nsec / BN) * ha.ssq_stride + m0 + row] = tot;
+      }
+    }
+    // A lane always takes the same two logical chunks (8 consecutive columns each), BN / 2 columns apart, of
+    // its rows, so its gains and channel-pair indices are fixed, and where BN / 2 is a multiple of the head
+    // width both chunks rotate by the same table entries.  The loads of a group of rows (staging tile,
+    // rotation table) are issued together.
+    constexpr int HC = CPR / 2, RP2 = 64 / HC, IT = BM / NW / RP2, G = 4;
+    static_assert(BM / NW % RP2 == 0, "rows per wavefront");
+    const int c8 = (lane % HC) * 8;                      // first column of chunk 0; chunk 1 starts at c8 + BN / 2
+    const bool rotate = !swapped && sc.rope, scale = !swapped && (sc.gain || sc.rope);
+    const bool share = (BN / 2) % ha.head_dim == 0;      // both chunks use the same channel pairs
+    const int half = ha.head_dim >> 1;
+    float gg[2][8];
+    int nn[2], p0[2];
+    bool col_ok[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+      nn[k] = (int)nsec + c8 + k * (BN / 2);             // first of the chunk's 8 channels inside the section
+      p0[k] = (nn[k] & hmask) >> 1;
+      col_ok[k] = n0 + c8 + k * (BN / 2) < N;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) gg[k][t] = 1.f;
+      if (!swapped && sc.gain && col_ok[k]) {
+        const float4 g0 = *(const float4*)(sc.gain + nn[k]), g1 = *(const float4*)(sc.gain + nn[k] + 4);
+        gg[k][0] = g0.x; gg[k][1] = g0.y; gg[k][2] = g0.z; gg[k][3] = g0.w;
+        gg[k][4] = g1.x; gg[k][5] = g1.y; gg[k][6] = g1.z; gg[k][7] = g1.w;
+      }
+    }
+#pragma unroll
+    for (int it0 = 0; it0 < IT; it0 += G) {
+      uint4 d[G][2];
+      float4 cs[G][2][2];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (it0 + g < IT) {
+          const int row = wave * (BM / NW) + (it0 + g) * RP2 + lane / HC;
+#pragma unroll
+          for (int k = 0; k < 2; ++k) {
+            d[g][k] = smem[row * CPR + (((c8 >> 3) + k * HC) ^ ((row & 31) >> 1))];
+            if (row & 1) d[g][k] = make_uint4(d[g][k].z, d[g][k].w, d[g][k].x, d[g][k].y);
+          }
+          if (rotate && m0 + row < M) {
+            const float4* t = (const float4*)(ha.cs + (m0 + row) * half + p0[0]);
+            cs[g][0][0] = t[0]; cs[g][0][1] = t[1];
+            if (!share) {
+              const float4* t1 = (const float4*)(ha.cs + (m0 + row) * half + p0[1]);
+              cs[g][1][0] = t1[0]; cs[g][1][1] = t1[1];
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (it0 + g < IT) {
+          const int row = wave * (BM / NW) + (it0 + g) * RP2 + lane / HC;
+#pragma unroll
+          for (int k = 0; k < 2; ++k) {
+            if (swapped) {
+              const int64_t ch = nsec + row, m = m0 + c8 + k * (BN / 2);   // channel in the section, first of 8 output rows
+              if (ch < ha.dim && n0 + row < N && m < M)
+                *(uint4*)((bf16_t*)sc.dst + ch * sc.ld + sc.row0 + m) = d[g][k];
+            } else if (m0 + row < M && col_ok[k]) {
+              const int64_t m = m0 + row;
+              uint4 dv = d[g][k];
+              if (scale) {
+                const uint32_t w[4] = {dv.x, dv.y, dv.z, dv.w};
+                const float4 c0 = cs[g][share ? 0 : k][0], c1 = cs[g][share ? 0 : k][1];
+                const float csv[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+                uint32_t o[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                  float a = bf16_to_f32((bf16_t)(w[u] & 0xffff)) * gg[k][2 * u], b = bf16_to_f32((bf16_t)(w[u] >> 16)) * gg[k][2 * u + 1];
+                  if (rotate) {
+                    const float a2 = a * csv[2 * u] - b * csv[2 * u + 1], b2 = a * csv[2 * u + 1] + b * csv[2 * u];
+                    a = a2; b = b2;
+                  }
+                  o[u] = cvt_pk_bf16(a, b);
+                }
+                dv = make_uint4(o[0], o[1], o[2], o[3]);
+              }
+              *(uint4*)((bf16_t*)sc.dst + (int64_t)(nn[k] >> hshift) * sc.ld + (sc.row0 + m) * ha.head_dim + (nn[k] & hmask)) = dv;
+            }
+          }
+        }
+      }
+    }
+  } else if constexpr (EPI != EPI_RESID) {
     constexpr int UPR = BN / 4;                          // 8-byte units (4 bf16) per LDS row
     constexpr int CPR = BN / 8, RPI = 64 / CPR;          // 16-byte chunks per row, rows per wavefront read
     // the whole tile at once if it fits the two operand buffers, else one wavefront row (WM rows) per pass
@@ -264,25 +436,62 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   }
 }
 
-template <int BM, int BN, int WGM, int WGN>
-static void launch_cfg(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
-                       int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
+template <int BM, int BN, int WGM, int WGN, int EPI>
+static void launch_one(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
+                       int64_t K, const EpiArgs& e, hipStream_t st) {
   constexpr int NT = WGM * WGN * 64;
   constexpr size_t lds = (size_t)(BM + BN) * 128 * 2;
   const int tm = (int)((M + BM - 1) / BM), tn = (int)((N + BN - 1) / BN);
-  static std::atomic<uint64_t> done[3];
-  if (epi == EPI_STORE) allow_dynamic_lds((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_STORE>, (int)lds, done[0]);
-  else if (epi == EPI_GELU) allow_dynamic_lds((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_GELU>, (int)lds, done[1]);
-  else allow_dynamic_lds((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID>, (int)lds, done[2]);
+  static std::atomic<uint64_t> done;
+  allow_dynamic_lds((const void*)k_gemm_bf16<BM, BN, WGM, WGN, EPI>, (int)lds, done);
+  HeadsArgs ha{};
+  if (EPI == EPI_HEADS) { e.heads->ssq_np = e.heads->dim / BN; ha = *e.heads; }
   dim3 grid((unsigned)((tm * tn + 7) / 8 * 8));
-  if (epi == EPI_STORE) k_gemm_bf16<BM, BN, WGM, WGN, EPI_STORE><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
-  else if (epi == EPI_GELU) k_gemm_bf16<BM, BN, WGM, WGN, EPI_GELU><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
-  else k_gemm_bf16<BM, BN, WGM, WGN, EPI_RESID><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e);
+  k_gemm_bf16<BM, BN, WGM, WGN, EPI><<<grid, NT, lds, st>>>(A, lda, Wt, ldw, M, N, K, tn, tm * tn, e, ha);
+}
+template <int BM, int BN, int WGM, int WGN>
+static void launch_cfg(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
+                       int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
+  if (epi == EPI_STORE) launch_one<BM, BN, WGM, WGN, EPI_STORE>(A, lda, Wt, ldw, M, N, K, e, st);
+  else if (epi == EPI_GELU) launch_one<BM, BN, WGM, WGN, EPI_GELU>(A, lda, Wt, ldw, M, N, K, e, st);
+  else launch_one<BM, BN, WGM, WGN, EPI_RESID>(A, lda, Wt, ldw, M, N, K, e, st);
 }
 
-void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
+// EPI_HEADS.  Sections must be whole tiles wide (dim % 256 == 0, or dim % 128 == 0 for problems small enough
+// for 128x128 tiles) and a transposed section needs a square tile, 8 | M and 8 | row0.
+bool gemm_bf16_heads_ok(int64_t M, int64_t N, const HeadsArgs& h) {
+  const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+  const int bn = t256 < 64 ? 128 : 256;
+  if (h.dim <= 0 || (h.head_dim != 64 && h.head_dim != 128) || h.dim % bn || h.dim % h.head_dim || N % h.dim || N / h.dim > 3) return false;
+  for (int i = 0; i < (int)(N / h.dim); ++i) {
+    if (h.sec[i].transposed && (M % 8 || h.sec[i].row0 % 8 || h.sec[i].ld % 8)) return false;
+    if (h.sec[i].ssq && h.ssq_stride < M) return false;
+  }
+  return true;
+}
+static void launch_gemm_bf16_heads(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
+                                   int64_t K, const EpiArgs& e, hipStream_t st) {
+  const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+  if (t256 < 64) { launch_one<128, 128, 2, 2, EPI_HEADS>(A, lda, Wt, ldw, M, N, K, e, st); return; }
+  bool any_t = false;
+  for (int i = 0; i < (int)(N / e.heads->dim); ++i) any_t = any_t || e.heads->sec[i].transposed;
+  // the 160-row tile cannot exchange its operands; it pays where it fills the one round better (see below)
+  const int64_t t160 = ((M + 159) / 160) * ((N + 255) / 256);
+  const bool fits160 = (M + 159) / 160 * 160 <= (M + 255) / 256 * 256;
+  if (!any_t && fits160 && 0.79 * (double)((t160 + 255) / 256) < (double)((t256 + 255) / 256))
+    launch_one<160, 256, 1, 8, EPI_HEADS>(A, lda, Wt, ldw, M, N, K, e, st);
+  else
+    launch_one<256, 256, 2, 4, EPI_HEADS>(A, lda, Wt, ldw, M, N, K, e, st);
+}
+
+bool launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
                       int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
-  if (M <= 0 || N <= 0) return;
+  if (M <= 0 || N <= 0) return true;
+  if (epi == EPI_HEADS) {
+    if (!e.heads || !gemm_bf16_heads_ok(M, N, *e.heads)) return false;
+    launch_gemm_bf16_heads(A, lda, Wt, ldw, M, N, K, e, st);
+    return true;
+  }
   // One block per CU at a time, so a launch costs ceil(blocks / 256) rounds of one block's duration.
   // 256x256 tiles are the default.  Other shapes are taken when rounds x relative duration comes out lower:
   // 192x256 (0.82 of a 256x256 tile), 160x256 (0.79; 1 x 8 wavefronts, more LDS reads per MFMA, but e.g. 39 x 6
@@ -293,14 +502,15 @@ void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ld
   const int64_t t192 = ((M + 191) / 192) * ((N + 255) / 256);
   const int64_t t160 = ((M + 159) / 160) * ((N + 255) / 256);
   const int64_t t320 = ((M + 319) / 320) * ((N + 255) / 256);
-  if (t256 < 64) { launch_cfg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
+  if (t256 < 64) { launch_cfg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
   const int64_t mpad = (M + 255) / 256 * 256;
   const double cost256 = (double)((t256 + 255) / 256), cost192 = 0.82 * (double)((t192 + 255) / 256);
   const double cost160 = (M + 159) / 160 * 160 <= mpad ? 0.79 * (double)((t160 + 255) / 256) : 1e30;
   const double cost320 = (M + 319) / 320 * 320 <= mpad ? 1.25 * (double)((t320 + 255) / 256) : 1e30;
   const double best = fmin(fmin(cost256, cost192), fmin(cost160, cost320));
-  if (best == cost256) { launch_cfg<256, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
-  if (best == cost160) { launch_cfg<160, 256, 1, 8>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
-  if (best == cost320) { launch_cfg<320, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return; }
+  if (best == cost256) { launch_cfg<256, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
+  if (best == cost160) { launch_cfg<160, 256, 1, 8>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
+  if (best == cost320) { launch_cfg<320, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
   launch_cfg<192, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st);
+  return true;
 }

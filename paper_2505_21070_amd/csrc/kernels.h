@@ -11,10 +11,6 @@ template <typename T>
 void launch_ln_modulate(const float* x, T* out, int64_t S, int D, float eps, const float* mul,
                         const float* add, int plus_one, hipStream_t st);
 
-struct RopeTables {            // cos/sin pairs: tab[pos][pair] = (cos, sin)
-  const float2* f; const float2* y; const float2* x;
-  int c_f, c_h, c_w;           // pairs per axis
-};
 // src[S, ld] holds un-normalised projections; job j takes columns [col, col+D) of every row:
 // dst[head][row0 + s][d] = out_scale * RoPE(RMSNorm_D(src[s, col:col+D]) * g) ; rope == 0 skips the rotation.
 // Up to two jobs (e.g. q and k of the fused QKV output) run in one launch.  D % 8 == 0.
@@ -24,6 +20,11 @@ template <typename T> struct NormRopeJob {
 template <typename T>
 void launch_norm_rope(const T* src, int64_t ld, int64_t S, int h, int d, float eps, const NormRopeJob<T>* jobs,
                       int n_jobs, const RopeTables* rope, int frame0, int tok_h, int tok_w, hipStream_t st);
+// cs[s][i] = rotation (cos, sin) of channel pair i < head_dim / 2 at token s of a block that starts at frame0
+void launch_rope_tokens(const RopeTables& rt, int frame0, int tok_h, int tok_w, int64_t S, float2* cs, hipStream_t st);
+// k[head][row0 + s][:] *= rsqrt(sum_i ssq[i * stride + s] / (h * d) + eps), bf16 rows of d elements, in place
+void launch_scale_rows_bf16(bf16_t* k, int64_t head_stride, int64_t row0, int64_t S, int h, int d, const float* ssq,
+                            int np, int64_t stride, float eps, hipStream_t st);
 // vt[head][c][col0 + s] = src[s, col + head*d + c]
 template <typename T>
 void launch_v_transpose(const T* src, int64_t ld, int col, int64_t S, int h, int d, T* vt,
@@ -85,8 +86,10 @@ inline void allow_dynamic_lds(const void* kernel, int bytes, std::atomic<uint64_
 
 // ---- gemm_bf16.hip : C = A[M,K] * Wt[N,K]^T (+ epilogue), bf16 MFMA, fp32 accumulate --------
 // A must be readable for roundup(M, 256) rows, Wt for roundup(N, 256) rows; K % 64 == 0.
-void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M,
+bool launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M,
                       int64_t N, int64_t K, int epi, const EpiArgs& e, hipStream_t st);
+// whether launch_gemm_bf16(.., EPI_HEADS, ..) can take this problem; if not it launches nothing and returns false
+bool gemm_bf16_heads_ok(int64_t M, int64_t N, const HeadsArgs& h);
 // ---- attn_bf16.hip : flash attention on MFMA, head_dim 64 or 128 ------------------------------
 // q must already be multiplied by log2(e)/sqrt(d) (attn_bf16_q_scale) and be readable for
 // roundup(S, 256) rows per head; k rows / vt columns readable (finite in vt) up to
@@ -94,7 +97,15 @@ void launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ld
 // scratch: attn_bf16_scratch_bytes(d) bytes of device memory for the partial results of work that is
 // split over key ranges (contents need not be kept between calls), or nullptr to never split.
 inline float attn_bf16_q_scale(int d) { return 1.4426950408889634f / sqrtf((float)d); }
+// Deferred RMSNorm of the queries: row s of q (all heads) is multiplied by
+// rsqrt(sum_i ssq[i * stride + s] * inv_dim + eps) * scale as it is loaded (ssq == nullptr: q is used as stored).
+struct AttnQNorm { const float* ssq; int np; int64_t stride; float inv_dim, eps, scale; };
+// test hook: q[head][s][:] of all heads, token-major fp32, scaled and rounded exactly as the attention kernel does
+void launch_gather_heads_qnorm(const bf16_t* src, int64_t head_stride, int64_t S, int h, int d, const AttnQNorm& qn,
+                               float* dst, hipStream_t st);
+// out[i] = a[i] * b[i]
+void launch_mul_f32(const float* a, const float* b, float* out, int64_t n, hipStream_t st);
 size_t attn_bf16_scratch_bytes(int d);
 void launch_attn_bf16(const bf16_t* q, int64_t q_head_stride, const bf16_t* k, int64_t k_head_stride,
                       int64_t k_row0, const bf16_t* vt, int64_t vt_row_stride, int64_t S, int64_t L,
-                      int h, int d, bf16_t* out, int64_t ldo, float* scratch, hipStream_t st);
+                      int h, int d, bf16_t* out, int64_t ldo, float* scratch, const AttnQNorm* qnorm, hipStream_t st);

@@ -40,6 +40,7 @@ struct LayerMem {
   float *gq, *gk, *cgq, *cgk, *ln3g, *ln3b;     // fp32 copies of the per-channel vectors
   void *kbuf, *vtbuf;                           // [h][Lpad][d], [h][d][Lpad]: rows / columns = key positions of the buffer
   void *tk, *tvt;                               // text keys [h][Ltpad][d], text values transposed [h][d][Ltpad]
+  void *tkq; float* cgqk;                       // heads_epi: text keys times the cross-attention query gains, and the gain product
   void *wqkv_t, *bqkv, *wo_t, *cwq_t, *cwo_t, *w1_t, *w2_t;   // bf16 path: weights as [out(pad 256), in]
 };
 
@@ -78,6 +79,9 @@ struct dp_stage {
   float2 *rope_f, *rope_y, *rope_x; RopeTables rt;
   void* tap_attn; float *tap_xself, *tap_xcross;
   float* attn_scratch;
+  // DP_BF16 with dim % 256 == 0: the q/k/v and cross-q projections write per head from their GEMM epilogues
+  // (gains and rotation applied there), leaving only the RMSNorm row scale, which arrives as partial sums
+  float *qssq, *kssq; float2* rope_tok; int ssq_np, cross_np = 0; bool heads_epi; bool launch_ok = true;
   // state
   // Key buffer geometry (rows of kbuf = columns of vtbuf, the same in every layer).  The last block's keys
   // sit at [blk0, blk0 + last_S); the feature cache is the sub-range [cache0, cache0 + cache_len) of it that
@@ -145,6 +149,11 @@ static size_t carve(dp_stage* s, void* base) {
   s->ctx_mid = cv.take(s->Ltpad * D * E);
   const int64_t kmax = c.text_dim > D ? c.text_dim : D;
   s->wtmp = bf ? cv.take(rup(D, 256) * kmax * E) : nullptr;
+  s->heads_epi = bf && D % 256 == 0;
+  s->ssq_np = (int)(D / 128);                         // most partial sums per row any tile shape produces
+  s->qssq = s->heads_epi ? (float*)cv.take(s->Smax * s->ssq_np * 4) : nullptr;
+  s->kssq = s->heads_epi ? (float*)cv.take(s->Smax * s->ssq_np * 4) : nullptr;
+  s->rope_tok = s->heads_epi ? (float2*)cv.take(s->Smax * (c.head_dim / 2) * 8) : nullptr;
   s->tau = (float*)cv.take(c.freq_dim * 4);
   s->e1 = (float*)cv.take(GEMV_MAX_SLICES * D * 4); s->e2 = (float*)cv.take(GEMV_MAX_SLICES * D * 4);   // sliced vectors
   s->e0 = (float*)cv.take(GEMV_MAX_SLICES * 6 * D * 4);
@@ -167,7 +176,10 @@ static size_t carve(dp_stage* s, void* base) {
     m.cgq = (float*)cv.take(D * 4); m.cgk = (float*)cv.take(D * 4);
     m.ln3g = (float*)cv.take(D * 4); m.ln3b = (float*)cv.take(D * 4);
     m.kbuf = cv.take(s->Lpad * D * E); m.vtbuf = cv.take(s->Lpad * D * E);
-    m.tk = cv.take(s->Ltpad * D * E); m.tvt = cv.take(s->Ltpad * D * E);
+    m.tk = cv.take(s->Ltpad * D * E);
+    m.tkq = s->heads_epi ? cv.take(s->Ltpad * D * E) : nullptr;
+    m.cgqk = s->heads_epi ? (float*)cv.take(D * 4) : nullptr;
+    m.tvt = cv.take(s->Ltpad * D * E);
   }
   const size_t zero_end = cv.off;      // everything up to here is zero-filled at init
   s->attn_scratch = bf ? (float*)cv.take(attn_bf16_scratch_bytes(c.head_dim)) : nullptr;
@@ -201,26 +213,27 @@ template <typename T> struct Path;
 template <> struct Path<float> {
   static float q_scale(int) { return 1.f; }             // the fp32 attention kernel scales by 1/sqrt(d) itself
   // y = x[M,K] * W[K,N] (+epilogue); `wt` unused
-  static void gemm(const void* A, int64_t lda, const void* W, const void* /*wt*/, int64_t M, int64_t N,
+  static bool gemm(const void* A, int64_t lda, const void* W, const void* /*wt*/, int64_t M, int64_t N,
                    int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
     launch_gemm_f32((const float*)A, lda, (const float*)W, N, M, N, K, epi, e, st);
+    return true;
   }
   static void attn(const void* q, int64_t qhs, const void* k, int64_t khs, int64_t row0, const void* vt,
                    int64_t vrs, int64_t S, int64_t L, int h, int d, void* out, int64_t ldo, float* /*scratch*/,
-                   hipStream_t st) {
+                   const AttnQNorm* /*qn*/, hipStream_t st) {
     launch_attn_f32((const float*)q, qhs, (const float*)k, khs, row0, (const float*)vt, vrs, S, L, h, d, (float*)out, ldo, st);
   }
 };
 template <> struct Path<bf16_t> {
   static float q_scale(int d) { return attn_bf16_q_scale(d); }   // queries carry log2(e)/sqrt(d)
-  static void gemm(const void* A, int64_t lda, const void* /*W*/, const void* wt, int64_t M, int64_t N,
+  static bool gemm(const void* A, int64_t lda, const void* /*W*/, const void* wt, int64_t M, int64_t N,
                    int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
-    launch_gemm_bf16((const bf16_t*)A, lda, (const bf16_t*)wt, K, M, N, K, epi, e, st);
+    return launch_gemm_bf16((const bf16_t*)A, lda, (const bf16_t*)wt, K, M, N, K, epi, e, st);
   }
   static void attn(const void* q, int64_t qhs, const void* k, int64_t khs, int64_t row0, const void* vt,
                    int64_t vrs, int64_t S, int64_t L, int h, int d, void* out, int64_t ldo, float* scratch,
-                   hipStream_t st) {
-    launch_attn_bf16((const bf16_t*)q, qhs, (const bf16_t*)k, khs, row0, (const bf16_t*)vt, vrs, S, L, h, d, (bf16_t*)out, ldo, scratch, st);
+                   const AttnQNorm* qn, hipStream_t st) {
+    launch_attn_bf16((const bf16_t*)q, qhs, (const bf16_t*)k, khs, row0, (const bf16_t*)vt, vrs, S, L, h, d, (bf16_t*)out, ldo, scratch, qn, st);
   }
 };
 
@@ -278,6 +291,12 @@ static void init_typed(dp_stage* s, const void* text, hipStream_t st) {
     Path<T>::gemm(ctx, D, w.cwk, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbk), st);
     { const NormRopeJob<T> jk{0, m.cgk, 1.f, (T*)m.tk, s->Ltpad * d, 0, 0};
       launch_norm_rope<T>((const T*)s->raw, D, Lt, h, d, c.eps, &jk, 1, nullptr, 0, 1, 1, st); }
+    if (s->heads_epi) {
+      // q.k with q = r (q_raw * cgq): the query gains move over to the keys, the row scale r to the attention kernel
+      launch_mul_f32(m.cgk, m.cgq, m.cgqk, D, st);
+      const NormRopeJob<T> jk{0, m.cgqk, 1.f, (T*)m.tkq, s->Ltpad * d, 0, 0};
+      launch_norm_rope<T>((const T*)s->raw, D, Lt, h, d, c.eps, &jk, 1, nullptr, 0, 1, 1, st);
+    }
     if (bf) launch_transpose_pad<T>((const T*)w.cwv, D, D, (T*)s->wtmp, rup(D, 256), st);
     Path<T>::gemm(ctx, D, w.cwv, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbv), st);
     launch_v_transpose<T>((const T*)s->raw, D, 0, Lt, h, d, (T*)m.tvt, s->Ltpad, 0, st);
@@ -347,40 +366,68 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
     else { blk0 = s->cache0 + s->cache_len; key0 = s->cache0; }
   }
   s->blk0 = blk0;
+  if (s->heads_epi) PROF(DP_PROF_NORM_ROPE, launch_rope_tokens(s->rt, frame0, c.tok_h, c.tok_w, S, s->rope_tok, st));
   for (int l = 0; l < c.n_layers; ++l) {
     const dp_layer_weights& w = s->lw[(size_t)l]; LayerMem& m = s->lm[(size_t)l];
     const float* md = s->mod + (int64_t)l * 6 * D;
     const float *sh1 = md, *sc1 = md + D, *g1 = md + 2 * D, *sh2 = md + 3 * D, *sc2 = md + 4 * D, *g2 = md + 5 * D;
     // --- self-attention over [cached K/V ; this block]
     PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, sc1, sh1, 1, st));
-    if (bf) {
-      PROF(DP_PROF_QKV_GEMM,
-           Path<T>::gemm(s->hbuf, D, nullptr, m.wqkv_t, S, 3 * D, D, EPI_STORE, epi_store(s->raw, 3 * D, m.bqkv), st));
+    AttnQNorm qn{s->qssq, 0, s->Smax, 1.f / (float)D, c.eps, Path<T>::q_scale(d)};
+    if (s->heads_epi) {
+      HeadsArgs ha{};
+      ha.dim = (int)D; ha.head_dim = d; ha.cs = s->rope_tok; ha.ssq_stride = s->Smax;
+      ha.sec[0] = HeadSection{s->qbuf, s->Spad * d, 0, m.gq, s->qssq, 1, 0};
+      ha.sec[1] = HeadSection{m.kbuf, kv_hs, blk0, m.gk, s->kssq, 1, 0};
+      ha.sec[2] = HeadSection{m.vtbuf, s->Lpad, blk0, nullptr, nullptr, 0, 1};
+      EpiArgs e = epi_store(nullptr, 0, m.bqkv);
+      e.heads = &ha;
+      PROF(DP_PROF_QKV_GEMM, s->launch_ok &= Path<T>::gemm(s->hbuf, D, nullptr, m.wqkv_t, S, 3 * D, D, EPI_HEADS, e, st));
+      qn.np = ha.ssq_np;
+      PROF(DP_PROF_NORM_ROPE, launch_scale_rows_bf16((bf16_t*)m.kbuf, kv_hs, blk0, S, h, d, s->kssq, ha.ssq_np, s->Smax, c.eps, st));
     } else {
-      PROF(DP_PROF_QKV_GEMM,
-           Path<T>::gemm(s->hbuf, D, w.wq, nullptr, S, D, D, EPI_STORE, epi_store(s->raw, 3 * D, w.bq), st);
-           Path<T>::gemm(s->hbuf, D, w.wk, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + D, 3 * D, w.bk), st);
-           Path<T>::gemm(s->hbuf, D, w.wv, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + 2 * D, 3 * D, w.bv), st));
+      if (bf) {
+        PROF(DP_PROF_QKV_GEMM,
+             Path<T>::gemm(s->hbuf, D, nullptr, m.wqkv_t, S, 3 * D, D, EPI_STORE, epi_store(s->raw, 3 * D, m.bqkv), st));
+      } else {
+        PROF(DP_PROF_QKV_GEMM,
+             Path<T>::gemm(s->hbuf, D, w.wq, nullptr, S, D, D, EPI_STORE, epi_store(s->raw, 3 * D, w.bq), st);
+             Path<T>::gemm(s->hbuf, D, w.wk, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + D, 3 * D, w.bk), st);
+             Path<T>::gemm(s->hbuf, D, w.wv, nullptr, S, D, D, EPI_STORE, epi_store((T*)s->raw + 2 * D, 3 * D, w.bv), st));
+      }
+      PROF(DP_PROF_NORM_ROPE,
+           const NormRopeJob<T> qk[2] = {{0, m.gq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, 1},
+                                         {(int)D, m.gk, 1.f, (T*)m.kbuf, kv_hs, blk0, 1}};
+           launch_norm_rope<T>((const T*)s->raw, 3 * D, S, h, d, c.eps, qk, 2, &s->rt, frame0, c.tok_h, c.tok_w, st);
+           launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, blk0, st));
     }
-    PROF(DP_PROF_NORM_ROPE,
-         const NormRopeJob<T> qk[2] = {{0, m.gq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, 1},
-                                       {(int)D, m.gk, 1.f, (T*)m.kbuf, kv_hs, blk0, 1}};
-         launch_norm_rope<T>((const T*)s->raw, 3 * D, S, h, d, c.eps, qk, 2, &s->rt, frame0, c.tok_h, c.tok_w, st);
-         launch_v_transpose<T>((const T*)s->raw, 3 * D, (int)(2 * D), S, h, d, (T*)m.vtbuf, s->Lpad, blk0, st));
     PROF(DP_PROF_SELF_ATTN,
          Path<T>::attn(s->qbuf, s->Spad * d, m.kbuf, kv_hs, key0, m.vtbuf, s->Lpad, S,
-                       s->cache_len + S, h, d, s->attn_o, D, s->attn_scratch, st));
+                       s->cache_len + S, h, d, s->attn_o, D, s->attn_scratch, s->heads_epi ? &qn : nullptr, st));
     if (s->tap_attn && l == c.n_layers - 1) launch_copy2d<T>((const T*)s->attn_o, 0, (T*)s->tap_attn, 0, 1, S * D, st);
     PROF(DP_PROF_OPROJ_GEMM, Path<T>::gemm(s->attn_o, D, w.wo, m.wo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.bo, g1), st));
     if (s->tap_xself && l == c.n_layers - 1) launch_copy2d<float>(s->xres, 0, s->tap_xself, 0, 1, S * D, st);
     // --- cross-attention to the text tokens
     PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, m.ln3g, m.ln3b, 0, st));
-    PROF(DP_PROF_CROSS_Q_GEMM, Path<T>::gemm(s->hbuf, D, w.cwq, m.cwq_t, S, D, D, EPI_STORE, epi_store(s->raw, D, w.cbq), st));
-    PROF(DP_PROF_NORM_ROPE,
-         const NormRopeJob<T> cq{0, m.cgq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, 0};
-         launch_norm_rope<T>((const T*)s->raw, D, S, h, d, c.eps, &cq, 1, nullptr, 0, 1, 1, st));
-    PROF(DP_PROF_CROSS_ATTN,
-         Path<T>::attn(s->qbuf, s->Spad * d, m.tk, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, s->attn_scratch, st));
+    if (s->heads_epi) {
+      HeadsArgs ha{};
+      ha.dim = (int)D; ha.head_dim = d; ha.ssq_stride = s->Smax;
+      ha.sec[0] = HeadSection{s->qbuf, s->Spad * d, 0, nullptr, s->qssq, 0, 0};
+      EpiArgs e = epi_store(nullptr, 0, w.cbq);
+      e.heads = &ha;
+      PROF(DP_PROF_CROSS_Q_GEMM, s->launch_ok &= Path<T>::gemm(s->hbuf, D, w.cwq, m.cwq_t, S, D, D, EPI_HEADS, e, st));
+      qn.np = ha.ssq_np;
+      s->cross_np = ha.ssq_np;
+      PROF(DP_PROF_CROSS_ATTN,
+           Path<T>::attn(s->qbuf, s->Spad * d, m.tkq, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, s->attn_scratch, &qn, st));
+    } else {
+      PROF(DP_PROF_CROSS_Q_GEMM, Path<T>::gemm(s->hbuf, D, w.cwq, m.cwq_t, S, D, D, EPI_STORE, epi_store(s->raw, D, w.cbq), st));
+      PROF(DP_PROF_NORM_ROPE,
+           const NormRopeJob<T> cq{0, m.cgq, Path<T>::q_scale(d), (T*)s->qbuf, s->Spad * d, 0, 0};
+           launch_norm_rope<T>((const T*)s->raw, D, S, h, d, c.eps, &cq, 1, nullptr, 0, 1, 1, st));
+      PROF(DP_PROF_CROSS_ATTN,
+           Path<T>::attn(s->qbuf, s->Spad * d, m.tk, s->Ltpad * d, 0, m.tvt, s->Ltpad, S, c.text_len, h, d, s->attn_o, D, s->attn_scratch, nullptr, st));
+    }
     PROF(DP_PROF_CROSS_O_GEMM, Path<T>::gemm(s->attn_o, D, w.cwo, m.cwo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.cbo, nullptr), st));
     if (s->tap_xcross && l == c.n_layers - 1) launch_copy2d<float>(s->xres, 0, s->tap_xcross, 0, 1, S * D, st);
     // --- FFN
@@ -401,10 +448,12 @@ extern "C" int dp_stage_forward(dp_stage_t* s, const void* x_in, void* x_out, in
   if (!(timestep == timestep)) return fail(DP_EINVAL, "dp_stage_forward: timestep is NaN");
   hipStream_t st = (hipStream_t)hip_stream;
   (void)hipGetLastError();
+  s->launch_ok = true;
   if (s->cfg.dtype == DP_BF16) forward_typed<bf16_t>(s, x_in, x_out, n_frames, frame0, timestep, st);
   else forward_typed<float>(s, x_in, x_out, n_frames, frame0, timestep, st);
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) return fail(DP_EHIP, "dp_stage_forward: %s", hipGetErrorString(err));
+  if (!s->launch_ok) return fail(DP_ESTATE, "dp_stage_forward: a projection's per-head epilogue did not fit its shape");
   s->last_frames = n_frames; s->last_S = s->tok * n_frames;
   return DP_OK;
 }
@@ -448,9 +497,16 @@ static int peek_typed(dp_stage* s, int what, int layer, float* dst, int64_t cap,
     case DP_PEEK_V: launch_gather_vt<T>((const T*)m.vtbuf, s->Lpad, s->blk0, n, h, d, dst, st); break;
     case DP_PEEK_CACHE_K: launch_gather_heads<T>((const T*)m.kbuf, s->Lpad * d, s->cache0, n, h, d, dst, st); break;
     case DP_PEEK_CACHE_V: launch_gather_vt<T>((const T*)m.vtbuf, s->Lpad, s->cache0, n, h, d, dst, st); break;
-    case DP_PEEK_TEXT_K: launch_gather_heads<T>((const T*)m.tk, s->Ltpad * d, 0, n, h, d, dst, st); break;
+    case DP_PEEK_TEXT_K: launch_gather_heads<T>((const T*)(s->heads_epi ? m.tkq : m.tk), s->Ltpad * d, 0, n, h, d, dst, st); break;
     case DP_PEEK_TEXT_V: launch_gather_vt<T>((const T*)m.tvt, s->Ltpad, 0, n, h, d, dst, st); break;
-    case DP_PEEK_Q: launch_gather_heads<T>((const T*)s->qbuf, s->Spad * d, 0, n, h, d, dst, st); break;
+    case DP_PEEK_Q:
+      if (s->heads_epi) {
+        const AttnQNorm qn{s->qssq, s->cross_np, s->Smax, 1.f / (float)D, c.eps, Path<T>::q_scale(d)};
+        launch_gather_heads_qnorm((const bf16_t*)s->qbuf, s->Spad * d, n, h, d, qn, dst, st);
+      } else {
+        launch_gather_heads<T>((const T*)s->qbuf, s->Spad * d, 0, n, h, d, dst, st);
+      }
+      break;
     case DP_PEEK_ATTN:
       if (!s->tap_attn) return fail(DP_ESTATE, "dp_stage_peek: needs debug_taps");
       launch_to_f32<T>((const T*)s->tap_attn, dst, n * D, st); break;
