@@ -5,6 +5,7 @@
 static inline int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 // ---------------------------------------------------------------- conversions
+// One thread per 8 elements (16 bytes of bf16, two 16-byte accesses of fp32) when pointers and length allow it.
 template <typename T>
 __global__ void k_to_f32(const T* __restrict__ in, float* __restrict__ out, int64_t n) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -17,13 +18,36 @@ __global__ void k_from_f32(const float* __restrict__ in, T* __restrict__ out, in
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < n; i += stride) Elem<T>::st(out + i, in[i]);
 }
+__global__ __launch_bounds__(256) void k_bf16_to_f32_x8(const uint4* __restrict__ in, float4* __restrict__ out, int64_t n8) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  const uint4 v = in[i];
+  out[2 * i] = make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                           __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+  out[2 * i + 1] = make_float4(__uint_as_float(v.z << 16), __uint_as_float(v.z & 0xffff0000u),
+                               __uint_as_float(v.w << 16), __uint_as_float(v.w & 0xffff0000u));
+}
+__global__ __launch_bounds__(256) void k_f32_to_bf16_x8(const float4* __restrict__ in, uint4* __restrict__ out, int64_t n8) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  const float4 a = in[2 * i], b = in[2 * i + 1];
+  out[i] = make_uint4(pack_bf16x2(a.x, a.y), pack_bf16x2(a.z, a.w), pack_bf16x2(b.x, b.y), pack_bf16x2(b.z, b.w));
+}
 template <typename T> void launch_to_f32(const T* in, float* out, int64_t n, hipStream_t st) {
   if (n <= 0) return;
+  if (sizeof(T) == 2 && n % 8 == 0 && (uintptr_t)in % 16 == 0 && (uintptr_t)out % 16 == 0) {
+    k_bf16_to_f32_x8<<<cdiv(n / 8, 256), 256, 0, st>>>((const uint4*)in, (float4*)out, n / 8);
+    return;
+  }
   int grid = cdiv(n, 256); if (grid > 8192) grid = 8192;
   k_to_f32<T><<<grid, 256, 0, st>>>(in, out, n);
 }
 template <typename T> void launch_from_f32(const float* in, T* out, int64_t n, hipStream_t st) {
   if (n <= 0) return;
+  if (sizeof(T) == 2 && n % 8 == 0 && (uintptr_t)in % 16 == 0 && (uintptr_t)out % 16 == 0) {
+    k_f32_to_bf16_x8<<<cdiv(n / 8, 256), 256, 0, st>>>((const float4*)in, (uint4*)out, n / 8);
+    return;
+  }
   int grid = cdiv(n, 256); if (grid > 8192) grid = 8192;
   k_from_f32<T><<<grid, 256, 0, st>>>(in, out, n);
 }

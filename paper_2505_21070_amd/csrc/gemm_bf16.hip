@@ -10,6 +10,8 @@
 //
 // The epilogue stages the output tile through LDS so that global memory is written (and, for the fp32
 // residual update, read) in whole rows, 16 bytes per lane.
+#include <type_traits>
+
 #include "kernels.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -28,6 +30,32 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float a, float b) {
 __device__ __forceinline__ float gelu_tanh_fast(float v) {
   const float u2 = -2.0f * 0.7978845608028654f * 1.4426950408889634f * (v + 0.044715f * v * v * v);   // -2u log2(e)
   return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u2));
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) { static_for<N - 1>(f); f(std::integral_constant<int, N - 1>{}); }
+}
+// The fragments of a k-step are read in the order A row-tile 0, B column-tiles 0 .. TN-1, A row-tiles 1 ..;
+// the MFMAs run row-tile by row-tile (n = i * TN + j).  Index of the last fragment MFMA n needs:
+template <int TN> constexpr int frag_need(int n) {
+  const int i = n / TN, j = n % TN, ia = i == 0 ? 0 : TN + i, ib = 1 + j;
+  return ia > ib ? ia : ib;
+}
+template <int TN> constexpr int frag_need_upto(int n) {
+  int m = -1;
+  for (int t = 0; t <= n; ++t) m = frag_need<TN>(t) > m ? frag_need<TN>(t) : m;
+  return m;
+}
+// reads k (issued behind MFMA first + k * (NM - first) / NR) that precede MFMA n
+template <int NM, int NR> constexpr int reads_before(int n, int first) {
+  int c = 0;
+  for (int k = 0; k < NR; ++k) c += first + k * (NM - first) / NR < n ? 1 : 0;
+  return c;
+}
+// wait until at most C of this wavefront's LDS operations are outstanding (the other counters are left alone)
+template <int C> __device__ __forceinline__ void lds_wait() {
+  if constexpr (C < 15) __builtin_amdgcn_s_waitcnt(0xC07F | (C << 8));
 }
 
 template <int BM, int BN, int WGM, int WGN, int EPI>
@@ -85,17 +113,17 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
     const int p = (wave * IB + i) * 64 + lane, row = p >> 3, ch = (p & 7) ^ ((row >> 1) & 7);
     gB[i] = pb + row * lpb + ch * 8;
   }
-  auto load_tile = [&](int kt, int bufi) __attribute__((always_inline)) {
+  // load instruction q < IA + IB of this wavefront's share of k-tile kt into stage bufi
+  auto load_part = [&](int kt, int bufi, int q) __attribute__((always_inline)) {
     if (kt >= KT) return;
     const int t = kt * 64;
     uint4* base = smem + bufi * STAGE;
-#pragma unroll
-    for (int i = 0; i < IA; ++i)
-      if (!A_RAGGED || (wave * IA + i) * 64 < BM * 8)
-        __builtin_amdgcn_global_load_lds((glb_void_t*)(gA[i] + t), (lds_void_t*)(base + (wave * IA + i) * 64), 16, 0, 0);
-#pragma unroll
-    for (int i = 0; i < IB; ++i)
-      __builtin_amdgcn_global_load_lds((glb_void_t*)(gB[i] + t), (lds_void_t*)(base + BM * 8 + (wave * IB + i) * 64), 16, 0, 0);
+    if (q < IA) {
+      if (!A_RAGGED || (wave * IA + q) * 64 < BM * 8)
+        __builtin_amdgcn_global_load_lds((glb_void_t*)(gA[q] + t), (lds_void_t*)(base + (wave * IA + q) * 64), 16, 0, 0);
+    } else {
+      __builtin_amdgcn_global_load_lds((glb_void_t*)(gB[q - IA] + t), (lds_void_t*)(base + BM * 8 + (wave * IB + q - IA) * 64), 16, 0, 0);
+    }
   };
 
   f32x16 acc[TM][TN];
@@ -114,49 +142,81 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   for (int j = 0; j < TN; ++j) brow[j] = wn * WN + j * 32 + lr;
 
   // Software pipeline.  k-tile kt+1 is in flight while k-tile kt is multiplied; the fragments of k-step
-  // ks+1 are read while the MFMAs of k-step ks run.  The barrier of an iteration sits before its last
-  // k-step, whose fragments are already in registers: behind it the buffer of k-tile kt is free for
-  // k-tile kt+2 and k-tile kt+1 has landed, so the first fragments of the next iteration are read there.
-  auto read_frags = [&](const uint4* buf, int ks, bf16x8* af, bf16x8* bfr) __attribute__((always_inline)) {
-    const int kc = ks * 2 + lg;
+  // ks+1 are read while the MFMAs of k-step ks run, one read behind each of the first MFMAs, in the order in
+  // which the next step's MFMAs first need them.  The LDS reads are issued through inline assembly and
+  // waited for with explicit counts: the compiler would wait for all outstanding reads before the first
+  // MFMA of a step (the last of them only two MFMAs old), which stalls a wavefront whenever the other
+  // wavefront of its SIMD is not there to fill the gap; here an MFMA waits only for the fragments it
+  // needs, issued most of a k-step earlier.  LDS returns reads in order, so "at most c reads outstanding"
+  // means every read but the c newest has landed.
+  constexpr int NM = TM * TN, NR = TM + TN;              // MFMAs and fragment reads per k-step
+  constexpr int NB = NM >= 8 ? 2 : 1;                    // MFMAs of the last k-step issued before the barrier
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_t*)smem;
+  static_assert(WM % 16 == 0 && WN % 16 == 0, "every fragment row of a lane has the same swizzle");
+  // chunk (ks * 2 + lg) ^ s of a row, s = (row >> 1) & 7 = (lr >> 1) & 7 for all of this lane's fragment rows,
+  // is at byte (ks * 32) ^ swz of the row
+  const uint32_t swz = (uint32_t)(lg ^ ((lr >> 1) & 7)) * 16;
+  uint32_t fbase[NR];                                    // fragment f: LDS byte offset of this lane's row in stage 0
 #pragma unroll
-    for (int i = 0; i < TM; ++i) af[i] = __builtin_bit_cast(bf16x8, buf[arow[i] * 8 + (kc ^ ((arow[i] >> 1) & 7))]);
-#pragma unroll
-    for (int j = 0; j < TN; ++j) bfr[j] = __builtin_bit_cast(bf16x8, buf[BM * 8 + brow[j] * 8 + (kc ^ ((brow[j] >> 1) & 7))]);
-  };
+  for (int f = 0; f < NR; ++f) {
+    const bool is_a = f == 0 || f > TN;
+    const int row = is_a ? arow[f == 0 ? 0 : f - TN] : brow[f - 1];
+    fbase[f] = lds0 + (uint32_t)((is_a ? 0 : BM * 8) + row * 8) * 16;
+  }
   bf16x8 af[2][TM], bfr[2][TN];
-  load_tile(0, 0);
+  // fragment f of k-step ks of the stage at byte offset `stage` into register buffer `to`
+  auto read_frag = [&](uint32_t stage, int ks, int f, int to) __attribute__((always_inline)) {
+    u32x4 v;
+    const uint32_t addr = fbase[f] + (stage + (swz ^ (uint32_t)(ks * 32)));
+    asm volatile("ds_read_b128 %0, %1" : "=&v"(v) : "v"(addr));
+    if (f == 0) af[to][0] = __builtin_bit_cast(bf16x8, v);
+    else if (f <= TN) bfr[to][f - 1] = __builtin_bit_cast(bf16x8, v);
+    else af[to][f - TN] = __builtin_bit_cast(bf16x8, v);
+  };
+  // The NL load instructions of a k-tile are spread, one behind an MFMA, over the NS MFMAs that follow the
+  // barrier which frees their stage (the rest of the last k-step and the first k-step of the next k-tile):
+  // issued together right behind the barrier they fill the vector-memory queue, and a wavefront that waits
+  // there to issue a load cannot issue the MFMAs behind it either.
+  constexpr int NL = IA + IB, NS = (NM - NB) + NM;
+#pragma unroll
+  for (int q = 0; q < NL; ++q) load_part(0, 0, q);
   tile_barrier();
-  load_tile(1, 1);
-  read_frags(smem, 0, af[0], bfr[0]);
+  static_for<NL>([&](auto q_) __attribute__((always_inline)) {
+    constexpr int q = decltype(q_)::value;
+    if constexpr (q * NS / NL < NM - NB) load_part(1, 1, q);           // the part that k-step 3 would have issued
+  });
+#pragma unroll
+  for (int f = 0; f < NR; ++f) read_frag(0, 0, f, 0);
   for (int kt = 0; kt < KT; ++kt) {
-    const uint4* buf = smem + (kt & 1) * STAGE;
+    const uint32_t cur = (uint32_t)(kt & 1) * STAGE * 16, nxt = (uint32_t)((kt + 1) & 1) * STAGE * 16;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      if (ks < 3) {
-        read_frags(buf, ks + 1, af[(ks + 1) & 1], bfr[(ks + 1) & 1]);
-      } else {
-        tile_barrier();
-        load_tile(kt + 2, kt & 1);
-        read_frags(smem + ((kt + 1) & 1) * STAGE, 0, af[0], bfr[0]);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
-      // issue order: the LDS reads (and, in the last k-step, the k-tile loads) are spread between the MFMAs
-      if (ks < 3) {
-#pragma unroll
-        for (int g = 0; g < TM + TN; ++g) {
-          __builtin_amdgcn_sched_group_barrier(0x008, (TM * TN) / (TM + TN), 0);
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      static_for<NM>([&](auto n_) __attribute__((always_inline)) {
+        constexpr int n = decltype(n_)::value, i = n / TN, j = n % TN;
+        constexpr int need = frag_need<TN>(n), prev = n == 0 ? -1 : frag_need_upto<TN>(n - 1);
+        if (ks < 3) {
+          // reads of step ks+1 issued so far in this step: those with k * NM / NR < n
+          if constexpr (need > prev) lds_wait<NR - 1 - need + reads_before<NM, NR>(n, 0)>();
+        } else {
+          if constexpr (n < NB) { if constexpr (need > prev) lds_wait<NR - 1 - need>(); }
+          if constexpr (n == NB) tile_barrier();           // every read of this k-tile has landed (lgkmcnt(0) precedes it)
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN - (TM + TN) * ((TM * TN) / (TM + TN)), 0);
-      }
-      __builtin_amdgcn_sched_barrier(0);      // nothing moves between k-steps: reads stay one step ahead
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
+        static_for<NR>([&](auto k_) __attribute__((always_inline)) {
+          constexpr int k = decltype(k_)::value;
+          if (ks < 3) { if constexpr (k * NM / NR == n) read_frag(cur, ks + 1, k, (ks + 1) & 1); }
+          else { if constexpr (n >= NB && NB + k * (NM - NB) / NR == n) read_frag(nxt, 0, k, 0); }
+        });
+        static_for<NL>([&](auto q_) __attribute__((always_inline)) {
+          constexpr int q = decltype(q_)::value, slot = q * NS / NL;       // MFMAs after the barrier
+          if (ks == 3) { if constexpr (n >= NB && slot == n - NB) load_part(kt + 2, kt & 1, q); }
+          else if (ks == 0) { if constexpr (slot == (NM - NB) + n) load_part(kt + 1, (kt + 1) & 1, q); }
+        });
+        __builtin_amdgcn_sched_barrier(0);               // keeps the MFMAs, reads, loads and waits in this order
+      });
     }
   }
+  lds_wait<0>();
 
   // Epilogue.  The MFMAs ran with the weight rows as the A operand, so a lane holds the output row
   // m = .. + lr and, per register quad q, the four consecutive columns n = .. + q*8 + lg*4 + (0..3).
