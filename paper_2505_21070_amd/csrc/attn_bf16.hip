@@ -55,6 +55,22 @@ template <int CR> __device__ __forceinline__ int kswz(int row) { return CR == 16
 // tile row -> key held in that row: bits 2 and 3 of the row index are exchanged
 __device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) { static_for<N - 1>(f); f(std::integral_constant<int, N - 1>{}); }
+}
+// wait until at most C of this wavefront's LDS operations are outstanding (the other counters are left alone)
+template <int C> __device__ __forceinline__ void lds_wait() {
+  if constexpr (C < 15) __builtin_amdgcn_s_waitcnt(0xC07F | (C << 8));
+}
+// 16 bytes at LDS byte address addr + OFF, through inline assembly: the compiler neither reorders it nor
+// waits for it, the caller does (lds_wait)
+template <int OFF> __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 template <int HD, int QG, int KG>
 __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q, int64_t q_head_stride,
                                                   const bf16_t* __restrict__ k, int64_t k_head_stride,
@@ -149,17 +165,18 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
     const int p = qt * (VCH / QG) + i * 64 + lane, row = p >> 3, ch = (p & 7) ^ ((row >> 1) & 7);
     voff[i] = row * (int)vt_row_stride + ch * 8;
   }
-  auto load_tile = [&](int tile, int bufi) __attribute__((always_inline)) {
-    const bf16_t* ks_ = kh + (int64_t)tile * 64 * HD;
-    const bf16_t* vs_ = vh + (int64_t)tile * 64;
-#pragma unroll
-    for (int i = 0; i < CK; ++i)
-      __builtin_amdgcn_global_load_lds((glb_void_t*)(ks_ + koff[i]),
+  // load instruction i of this wavefront's share of a tile: the K part first (i < CK), then the V^T part
+  auto load_part = [&](int tile, int bufi, int i) __attribute__((always_inline)) {
+    if (i < CK)
+      __builtin_amdgcn_global_load_lds((glb_void_t*)(kh + (int64_t)tile * 64 * HD + koff[i]),
                                        (lds_void_t*)(kbuf + bufi * KCH + qt * (KCH / QG) + i * 64), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds((glb_void_t*)(vh + (int64_t)tile * 64 + voff[i - CK]),
+                                       (lds_void_t*)(vbuf + bufi * VCH + qt * (VCH / QG) + (i - CK) * 64), 16, 0, 0);
+  };
+  auto load_tile = [&](int tile, int bufi) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < CV; ++i)
-      __builtin_amdgcn_global_load_lds((glb_void_t*)(vs_ + voff[i]),
-                                       (lds_void_t*)(vbuf + bufi * VCH + qt * (VCH / QG) + i * 64), 16, 0, 0);
+    for (int i = 0; i < CK + CV; ++i) load_part(tile, bufi, i);
   };
 
   f32x16 oacc[DT], negm;
@@ -270,7 +287,164 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
     return fresh;
   };
 
-  pass(std::false_type{});
+
+  // Fast pass (fixed reference).  Per tile a wavefront issues NMF MFMAs in the order S^T of the first 32-key
+  // half, S^T of the second half, O^T += V^T P^T of the first half, then of the second; the exponentials of
+  // the first half are issued between the MFMAs of the second half's S^T and those of the second half
+  // between the first half's V^T P^T MFMAs, so the vector unit works while the matrix pipe runs.  Every MFMA
+  // takes one operand fragment from LDS; fragment i + PD is read right behind MFMA i, through inline
+  // assembly with explicit waits (LDS returns reads in order), so an MFMA never waits for a read issued
+  // just before it.  The tile's barrier sits PD MFMAs before the tile's end, once all its fragments are in
+  // registers: behind it the loads of the tile after next and the first PD fragment reads of the next tile
+  // go out between the remaining MFMAs.
+  constexpr int NMF = 2 * (KS + 2 * DT), PD = 4, PPM = 8 / KS;      // MFMAs per tile, read-ahead, exp pairs per MFMA
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_void_t*)smem;
+  // This lane's row of a K tile (row lr of a 32-key half) and of a V^T tile (row lr of a 32-channel group) in
+  // buffer 0, as LDS byte addresses; chunk c of the row sits at byte (c * 16) ^ swizzle, and c = ks*2 + lg or
+  // (a*2+u)*2 + lg has lg as its lowest bit, so the lane-dependent part of the XOR is one constant per tile kind.
+  const uint32_t krow = lds0 + (uint32_t)(kg * GCH + lr * CR) * 16, kx = (uint32_t)(lg ^ kswz<CR>(lr)) * 16;
+  const uint32_t vrow = lds0 + (uint32_t)(kg * GCH + NBUF * KCH + lr * 8) * 16, vx = (uint32_t)(lg ^ ((lr >> 1) & 7)) * 16;
+  // operand fragment of MFMA i of a tile whose K / V^T buffers start kbo / vbo bytes behind buffer 0
+  auto frag_read = [&](auto i_, uint32_t kbo, uint32_t vbo) __attribute__((always_inline)) {
+    constexpr int i = decltype(i_)::value;
+    if constexpr (i < 2 * KS) {
+      return lds_read16<(i / KS) * 32 * CR * 16>((krow + kbo) + (kx ^ (uint32_t)((i % KS) * 32)));
+    } else {
+      constexpr int j = i - 2 * KS, a = j / (2 * DT), u = (j % (2 * DT)) / DT, dt = j % DT;
+      return lds_read16<dt * 32 * 8 * 16>((vrow + vbo) + (vx ^ (uint32_t)((a * 2 + u) * 32)));
+    }
+  };
+  auto pass_fast = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int a = 0; a < DT; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[a][r] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[r] = 0.f;
+    mrun = 0.f; lsum = 0.f;
+    // Step j of this pass works on tile cnt - 1 - j of the range (the sums do not care about the order), in
+    // buffer j % NBUF: the last tile of the range, the only one that can be ragged, comes first and is done
+    // here in plain order with its keys at or beyond L masked; the pinned loop below then sees whole tiles only.
+    if (cnt > 0) load_tile(cnt - 1, 0);
+    if (cnt > 1) load_tile(cnt - 2, 1);
+    tile_barrier();
+    if (cnt > 0) {
+      const int kvalid = (int)(L - (int64_t)(first + cnt - 1) * 64);   // >= 1; < 64 only in a ragged tile
+      // reference = maximum over the tile's first 32 keys (the valid ones of them).  Register r of lane group
+      // lg is tile row a*32 + (r/4)*8 + lg*4 + r%4, which holds key swap23(row).
+      f32x16 sv;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const int row = lr, ch = ks * 2 + lg;
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, kbuf[row * CR + (ch ^ kswz<CR>(row))]);
+        sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? negm : sv, 0, 0, 0);
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (swap23((r >> 2) * 8 + lg * 4 + (r & 3)) < kvalid) mx = fmaxf(mx, sv[r]);
+      mrun = fmaxf(mx, __shfl_xor(mx, 32, 64));
+#pragma unroll
+      for (int r = 0; r < 16; ++r) negm[r] = -mrun;
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        if (a == 0) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sv[r] -= mrun;
+        } else {
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const int row = 32 + lr, ch = ks * 2 + lg;
+            const bf16x8 kf = __builtin_bit_cast(bf16x8, kbuf[row * CR + (ch ^ kswz<CR>(row))]);
+            sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], ks == 0 ? negm : sv, 0, 0, 0);
+          }
+        }
+        if (kvalid < 64) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (swap23(a * 32 + (r >> 2) * 8 + lg * 4 + (r & 3)) >= kvalid) sv[r] = -INFINITY;
+        }
+        uint4 pf[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          uint32_t w[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            w[j] = cvt_pk_bf16(__builtin_amdgcn_exp2f(sv[u * 8 + 2 * j]), __builtin_amdgcn_exp2f(sv[u * 8 + 2 * j + 1]));
+            lsum = add_pk_bf16(w[j], lsum);
+          }
+          pf[u] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            const int row = dt * 32 + lr, ch = (a * 2 + u) * 2 + lg;
+            const bf16x8 vf = __builtin_bit_cast(bf16x8, vbuf[row * 8 + (ch ^ ((row >> 1) & 7))]);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pf[u]), oacc[dt], 0, 0, 0);
+          }
+      }
+    }
+    tile_barrier();                 // every wavefront is done with buffer 0
+    if (cnt > 2) load_tile(cnt - 3, 0);
+    bf16x8 fr[PD];
+    f32x16 sacc[2];
+    uint32_t pw[2][8];              // P of the two halves: packed bf16 pairs, four per MFMA operand
+    static_for<PD>([&](auto i_) __attribute__((always_inline)) {
+      fr[decltype(i_)::value] = frag_read(i_, (uint32_t)(1 % NBUF) * KCH * 16, (uint32_t)(1 % NBUF) * VCH * 16);
+    });
+    // exponentials of scores 2p, 2p+1 of half a, packed; row sums from the rounded values
+    auto e_piece = [&](int a, int pidx) __attribute__((always_inline)) {
+      pw[a][pidx] = cvt_pk_bf16(__builtin_amdgcn_exp2f(sacc[a][2 * pidx]), __builtin_amdgcn_exp2f(sacc[a][2 * pidx + 1]));
+      lsum = add_pk_bf16(pw[a][pidx], lsum);
+    };
+    for (int j = 1; j < n0; ++j) {
+      if (j < cnt) {
+        const uint32_t kbo = (uint32_t)(j % NBUF) * KCH * 16, vbo = (uint32_t)(j % NBUF) * VCH * 16;
+        const uint32_t kbn = (uint32_t)((j + 1) % NBUF) * KCH * 16, vbn = (uint32_t)((j + 1) % NBUF) * VCH * 16;
+        static_for<NMF>([&](auto i_) __attribute__((always_inline)) {
+          constexpr int i = decltype(i_)::value;
+          if constexpr (i < NMF - PD) lds_wait<PD - 1>();               // fragment i has landed
+          __builtin_amdgcn_sched_barrier(0);                            // the MFMA stays behind the wait
+          if constexpr (i < KS) {
+            sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % PD], qf[i], i == 0 ? negm : sacc[0], 0, 0, 0);
+          } else if constexpr (i < 2 * KS) {
+            sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % PD], qf[i - KS], i == KS ? negm : sacc[1], 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < PPM; ++e) e_piece(0, (i - KS) * PPM + e);
+          } else {
+            constexpr int m = i - 2 * KS, a = m / (2 * DT), u = (m % (2 * DT)) / DT, dt = m % DT;
+            const uint4 pf = make_uint4(pw[a][u * 4], pw[a][u * 4 + 1], pw[a][u * 4 + 2], pw[a][u * 4 + 3]);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i % PD], __builtin_bit_cast(bf16x8, pf), oacc[dt], 0, 0, 0);
+            if constexpr (a == 0) {
+#pragma unroll
+              for (int e = 0; e < PPM; ++e) e_piece(1, m * PPM + e);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);      // the read that reuses the MFMA's operand register stays behind it
+          if constexpr (i + PD < NMF) fr[i % PD] = frag_read(std::integral_constant<int, i + PD>{}, kbo, vbo);
+          if constexpr (i == NMF - PD - 1) {
+            lds_wait<0>();          // every fragment of this tile is in registers
+            tile_barrier();         // the next tile has landed and every wavefront is done reading this one
+          }
+          if constexpr (i >= NMF - PD) {
+            if (j + 2 < cnt) {
+#pragma unroll
+              for (int q = 0; q < CK + CV; ++q)
+                if (q * PD / (CK + CV) == i - (NMF - PD)) load_part(cnt - 3 - j, j % NBUF, q);
+            }
+            fr[i % PD] = frag_read(std::integral_constant<int, i + PD - NMF>{}, kbn, vbn);
+          }
+          __builtin_amdgcn_sched_barrier(0);                            // keeps this order
+        });
+      } else {
+        tile_barrier();
+      }
+    }
+    lds_wait<0>();
+  };
+
+  pass_fast();
   const bool empty = cnt == 0;                          // this key group has no tile (a single-tile key range)
   float ltot = lsum + __shfl_xor(lsum, 32, 64);
   if (__syncthreads_or(!empty && !(ltot <= 0x1p100f))) {  // overflow somewhere in the block: redo it safely

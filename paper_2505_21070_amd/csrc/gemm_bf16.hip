@@ -201,6 +201,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
           if constexpr (n < NB) { if constexpr (need > prev) lds_wait<NR - 1 - need>(); }
           if constexpr (n == NB) tile_barrier();           // every read of this k-tile has landed (lgkmcnt(0) precedes it)
         }
+        __builtin_amdgcn_sched_barrier(0);               // the MFMA stays behind the wait for its fragments
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
         static_for<NR>([&](auto k_) __attribute__((always_inline)) {
           constexpr int k = decltype(k_)::value;
