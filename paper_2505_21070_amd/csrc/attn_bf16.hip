@@ -421,6 +421,9 @@ __global__ __launch_bounds__(512) void k_attn_bf16(const bf16_t* __restrict__ q,
               for (int e = 0; e < PPM; ++e) e_piece(1, m * PPM + e);
             }
           }
+          // the two dependent S^T chains go first in the SIMD's issue arbitration (measured: 2 % over no hint)
+          if constexpr (i == 0) __builtin_amdgcn_s_setprio(1);
+          if constexpr (i == 2 * KS - 1) __builtin_amdgcn_s_setprio(0);
           __builtin_amdgcn_sched_barrier(0);      // the read that reuses the MFMA's operand register stays behind it
           if constexpr (i + PD < NMF) fr[i % PD] = frag_read(std::integral_constant<int, i + PD>{}, kbo, vbo);
           if constexpr (i == NMF - PD - 1) {

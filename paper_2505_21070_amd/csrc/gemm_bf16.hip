@@ -539,7 +539,7 @@ static void launch_gemm_bf16_heads(const bf16_t* A, int64_t lda, const bf16_t* W
   // the 160-row tile cannot exchange its operands; it pays where it fills the one round better (see below)
   const int64_t t160 = ((M + 159) / 160) * ((N + 255) / 256);
   const bool fits160 = (M + 159) / 160 * 160 <= (M + 255) / 256 * 256;
-  if (!any_t && fits160 && 0.79 * (double)((t160 + 255) / 256) < (double)((t256 + 255) / 256))
+  if (!any_t && fits160 && 0.80 * (double)((t160 + 255) / 256) < (double)((t256 + 255) / 256))
     launch_one<160, 256, 1, 8, EPI_HEADS>(A, lda, Wt, ldw, M, N, K, e, st);
   else
     launch_one<256, 256, 2, 4, EPI_HEADS>(A, lda, Wt, ldw, M, N, K, e, st);
@@ -555,7 +555,7 @@ bool launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ld
   }
   // One block per CU at a time, so a launch costs ceil(blocks / 256) rounds of one block's duration.
   // 256x256 tiles are the default.  Other shapes are taken when rounds x relative duration comes out lower:
-  // 192x256 (0.82 of a 256x256 tile), 160x256 (0.79; 1 x 8 wavefronts, more LDS reads per MFMA, but e.g. 39 x 6
+  // 192x256 (0.88 of a 256x256 tile), 160x256 (0.80; 1 x 8 wavefronts, more LDS reads per MFMA, but e.g. 39 x 6
   // tiles fill one round where 33 x 6 leave 58 CUs idle) and 320x256 (1.25, fewer operand bytes per flop).
   // The 160- and 320-row tiles read rows beyond M up to their own multiple, so they are used only where
   // that stays inside the 256-row padding the caller guarantees.  Tiny problems take 128x128 tiles.
@@ -565,13 +565,14 @@ bool launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ld
   const int64_t t320 = ((M + 319) / 320) * ((N + 255) / 256);
   if (t256 < 64) { launch_cfg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
   const int64_t mpad = (M + 255) / 256 * 256;
-  const double cost256 = (double)((t256 + 255) / 256), cost192 = 0.82 * (double)((t192 + 255) / 256);
-  const double cost160 = (M + 159) / 160 * 160 <= mpad ? 0.79 * (double)((t160 + 255) / 256) : 1e30;
+  const double cost256 = (double)((t256 + 255) / 256), cost192 = 0.88 * (double)((t192 + 255) / 256);
+  const double cost160 = (M + 159) / 160 * 160 <= mpad ? 0.80 * (double)((t160 + 255) / 256) : 1e30;
   const double cost320 = (M + 319) / 320 * 320 <= mpad ? 1.25 * (double)((t320 + 255) / 256) : 1e30;
   const double best = fmin(fmin(cost256, cost192), fmin(cost160, cost320));
+  // on a tie the taller tile wins: fewer operand bytes per flop
+  if (best == cost320) { launch_cfg<320, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
   if (best == cost256) { launch_cfg<256, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
   if (best == cost160) { launch_cfg<160, 256, 1, 8>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
-  if (best == cost320) { launch_cfg<320, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
   launch_cfg<192, 256, 2, 4>(A, lda, Wt, ldw, M, N, K, epi, e, st);
   return true;
 }
