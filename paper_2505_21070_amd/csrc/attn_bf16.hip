@@ -24,7 +24,9 @@
 // merged through LDS at the end, which halves the length of a block.  QG = 8, KG = 1 (everything else,
 // self- and cross-attention at full size): all 8 wavefronts share every K / V^T tile, so a tile brought
 // into LDS serves 256 queries and the LDS fill traffic per query halves.  Tiles hold 64 keys, are double-buffered and are loaded
-// HBM -> LDS directly.  Two wavefronts per SIMD hide each other's LDS and matrix-core latencies.
+// HBM -> LDS directly.  The two wavefronts of a SIMD are served oldest first rather than interleaved, so the
+// fast pass pins its issue order so that one wavefront alone keeps the matrix pipe busy: exponentials
+// between MFMAs, operand fragments read from LDS several MFMAs ahead with exact waits (see pass_fast).
 //
 // Grid: one block fits per compute unit, so a grid runs in rounds of 256 blocks.  The work ids that
 // would make up a last, partly filled round are instead cut into several key ranges each, one block per

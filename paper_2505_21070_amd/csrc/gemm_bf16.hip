@@ -4,12 +4,17 @@
 // Block tile BM x BN x 64, WGM x WGN wavefronts, each owning a (BM/WGM) x (BN/WGN) sub-tile built from
 // v_mfma_f32_32x32x16_bf16.  k-tiles go HBM -> LDS directly (no staging registers, no LDS stores) into
 // two buffers: k-tile kt+1 is in flight while k-tile kt is multiplied.  Operand fragments are
-// double-buffered in registers: those of k-step ks+1 are read from LDS while the MFMAs of k-step ks run.  LDS rows are 128 bytes (64 bf16); LDS serves 16 lanes
-// x 16 bytes per cycle from 64 banks, i.e. two rows per bank sweep, so the 16-byte chunk index is
-// XOR-swizzled with (row >> 1) & 7, which spreads a column of chunks over all banks.
+// double-buffered in registers: those of k-step ks+1 are read from LDS while the MFMAs of k-step ks run.
+// The issue order of the main loop is pinned (see there): the two wavefronts of a SIMD are served oldest
+// first rather than interleaved, so each has to keep the matrix pipe busy on its own; tile loads go out
+// one behind an MFMA instead of in a burst, and an MFMA waits only for the LDS reads it needs.
+// LDS rows are 128 bytes (64 bf16); LDS serves 16 lanes x 16 bytes per cycle from 64 banks, i.e. two rows per
+// bank sweep, so the 16-byte chunk index is XOR-swizzled with (row >> 1) & 7, which spreads a column of
+// chunks over all banks.
 //
 // The epilogue stages the output tile through LDS so that global memory is written (and, for the fp32
-// residual update, read) in whole rows, 16 bytes per lane.
+// residual update, read) in whole rows, 16 bytes per lane.  EPI_HEADS stores per attention head (q | k | v
+// sections: channel gains, 3D rotation, transposed V, row sums of squares for a deferred RMSNorm).
 #include <type_traits>
 
 #include "kernels.h"

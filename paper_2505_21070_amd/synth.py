@@ -34,6 +34,10 @@ CONFIGS = {
     # head_dim 64, with its work ids cut into two key ranges
     "wide64_bf16": dict(n_layers=1, dim=1024, n_heads=16, head_dim=64, ffn_dim=1024, text_len=32, text_dim=1024,
                         tok_h=16, tok_w=16, block_frames=8, cache_frames=2, dtype="bf16"),
+    # head_dim 128 with enough rows and columns for the GEMM's 256 x 256 tiles (72 of them in the fused
+    # q|k|v projection, whose epilogue writes per head) and the attention kernel's 256-query blocks
+    "wide128_bf16": dict(n_layers=1, dim=768, n_heads=6, head_dim=128, ffn_dim=1024, text_len=48, text_dim=768,
+                         tok_h=16, tok_w=16, block_frames=8, cache_frames=2, dtype="bf16"),
     # Wan-1.3B-shaped stage: 4 of 30 layers, 4 frames x 30x52 tokens + 2 cached frames
     "wan1p3b_stage": dict(n_layers=4, dim=1536, n_heads=12, head_dim=128, ffn_dim=8960, text_len=512,
                           text_dim=4096, tok_h=30, tok_w=52, block_frames=4, cache_frames=2, dtype="bf16"),

@@ -64,7 +64,7 @@ def test_tiny_fp32_stage(seed, strong_gate):
     print(f"tiny fp32 seed {seed} strong_gate {strong_gate}: worst max_abs {worst:.3e}")
 
 
-@pytest.mark.parametrize("name", ["tiny_bf16", "small_bf16", "longkv_bf16", "wide64_bf16"])
+@pytest.mark.parametrize("name", ["tiny_bf16", "small_bf16", "longkv_bf16", "wide64_bf16", "wide128_bf16"])
 @pytest.mark.parametrize("strong_gate", [False, True])
 def test_small_bf16_stage(name, strong_gate):
     rep = {}
