@@ -57,20 +57,8 @@ template <int CR> __device__ __forceinline__ int kswz(int row) { return CR == 16
 // tile row -> key held in that row: bits 2 and 3 of the row index are exchanged
 __device__ __forceinline__ int swap23(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-template <int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (N > 0) { static_for<N - 1>(f); f(std::integral_constant<int, N - 1>{}); }
-}
-// wait until at most C of this wavefront's LDS operations are outstanding (the other counters are left alone)
-template <int C> __device__ __forceinline__ void lds_wait() {
-  if constexpr (C < 15) __builtin_amdgcn_s_waitcnt(0xC07F | (C << 8));
-}
-// 16 bytes at LDS byte address addr + OFF, through inline assembly: the compiler neither reorders it nor
-// waits for it, the caller does (lds_wait)
 template <int OFF> __device__ __forceinline__ bf16x8 lds_read16(uint32_t addr) {
-  u32x4 v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
-  return __builtin_bit_cast(bf16x8, v);
+  return __builtin_bit_cast(bf16x8, lds_read16_raw<OFF>(addr));
 }
 
 template <int HD, int QG, int KG>

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 typedef uint16_t bf16_t;   // storage of a bfloat16: the upper half of an IEEE float
 
@@ -34,6 +35,26 @@ template <> struct Elem<bf16_t> {
 __device__ __forceinline__ void tile_barrier() {
   __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt = 0, expcnt = 7 and lgkmcnt = 15 (no wait)
   __syncthreads();
+}
+
+
+// ---- hand-scheduled loops: compile-time unrolling, LDS reads the compiler does not track, exact waits
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}) in this order
+template <int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) { static_for<N - 1>(f); f(std::integral_constant<int, N - 1>{}); }
+}
+// wait until at most C of this wavefront's LDS operations are outstanding (the other counters are left alone);
+// LDS operations complete in order, so everything but the C newest has then landed
+template <int C> __device__ __forceinline__ void lds_wait() {
+  if constexpr (C < 15) __builtin_amdgcn_s_waitcnt(0xC07F | (C << 8));
+}
+// 16 bytes at LDS byte address addr + OFF through inline assembly: the compiler neither moves it nor waits for
+// it; the caller does (lds_wait) before the first use of the result
+template <int OFF> __device__ __forceinline__ u32x4 lds_read16_raw(uint32_t addr) {
+  u32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=&v"(v) : "v"(addr), "n"(OFF));
+  return v;
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

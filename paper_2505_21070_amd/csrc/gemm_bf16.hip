@@ -15,8 +15,6 @@
 // The epilogue stages the output tile through LDS so that global memory is written (and, for the fp32
 // residual update, read) in whole rows, 16 bytes per lane.  EPI_HEADS stores per attention head (q | k | v
 // sections: channel gains, 3D rotation, transposed V, row sums of squares for a deferred RMSNorm).
-#include <type_traits>
-
 #include "kernels.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -37,10 +35,6 @@ __device__ __forceinline__ float gelu_tanh_fast(float v) {
   return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(u2));
 }
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-template <int N, typename F> __device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (N > 0) { static_for<N - 1>(f); f(std::integral_constant<int, N - 1>{}); }
-}
 // The fragments of a k-step are read in the order A row-tile 0, B column-tiles 0 .. TN-1, A row-tiles 1 ..;
 // the MFMAs run row-tile by row-tile (n = i * TN + j).  Index of the last fragment MFMA n needs:
 template <int TN> constexpr int frag_need(int n) {
@@ -58,11 +52,6 @@ template <int NM, int NR> constexpr int reads_before(int n, int first) {
   for (int k = 0; k < NR; ++k) c += first + k * (NM - first) / NR < n ? 1 : 0;
   return c;
 }
-// wait until at most C of this wavefront's LDS operations are outstanding (the other counters are left alone)
-template <int C> __device__ __forceinline__ void lds_wait() {
-  if constexpr (C < 15) __builtin_amdgcn_s_waitcnt(0xC07F | (C << 8));
-}
-
 template <int BM, int BN, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __restrict__ A, int64_t lda,
                                                              const bf16_t* __restrict__ Bt, int64_t ldb,
@@ -171,9 +160,7 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
   bf16x8 af[2][TM], bfr[2][TN];
   // fragment f of k-step ks of the stage at byte offset `stage` into register buffer `to`
   auto read_frag = [&](uint32_t stage, int ks, int f, int to) __attribute__((always_inline)) {
-    u32x4 v;
-    const uint32_t addr = fbase[f] + (stage + (swz ^ (uint32_t)(ks * 32)));
-    asm volatile("ds_read_b128 %0, %1" : "=&v"(v) : "v"(addr));
+    const u32x4 v = lds_read16_raw<0>(fbase[f] + (stage + (swz ^ (uint32_t)(ks * 32))));
     if (f == 0) af[to][0] = __builtin_bit_cast(bf16x8, v);
     else if (f <= TN) bfr[to][f - 1] = __builtin_bit_cast(bf16x8, v);
     else af[to][f - TN] = __builtin_bit_cast(bf16x8, v);
