@@ -147,3 +147,26 @@ def test_wan1p3b_full_queue_sweep_properties():
                         None, rows=np.array([0]))
     check("queue/cache_k_layer1", to_np(g.peek("cache_k", 0))[:tok][rows], k1[rows], "bf16")
     check("queue/cache_v_layer1", to_np(g.peek("cache_v", 0))[:tok][rows], v1[rows], "bf16")
+
+
+@pytest.mark.parametrize("name", ["wan1p3b_stage", "wide64_bf16"])
+def test_forward_is_bit_reproducible(name):
+    """The kernels use no atomics and a fixed summation order, and their hand-placed waits and barriers must
+    order every LDS tile hand-over: the same call on the same state has to return the same bits every time
+    (a missing wait would show up here as run-to-run differences).  Bench shape and a head_dim-64 shape."""
+    cfg, w, text, blocks = synth.make_case(name, seed=3, strong_gate=True)
+    nf, nc = cfg["block_frames"], cfg["cache_frames"]
+    g = gpu_stage(cfg, w, text, max_abs_frames=16)
+    x_nb, x_cur = to_dev(blocks[0], cfg), to_dev(blocks[1], cfg)
+    outs, keys = [], []
+    for _ in range(4):
+        g.cache_update(0, 0)                     # same state every time: the neighbour runs without a cache
+        g.forward(x_nb, nf, nf, 625.0)
+        g.cache_update(0, nc)
+        y = g.forward(x_cur, nf, 0, 500.0)
+        outs.append(y.clone())
+        keys.append(g.peek("k", cfg["n_layers"] - 1).clone())
+    for y, k in zip(outs[1:], keys[1:]):
+        assert torch.equal(y, outs[0])
+        assert torch.equal(k, keys[0])
+    assert torch.isfinite(outs[0].float()).all()
