@@ -549,7 +549,7 @@ bool launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ld
   // 256x256 tiles are the default.  Other shapes are taken when rounds x relative duration comes out lower:
   // 192x256 (0.88 of a 256x256 tile), 160x256 (0.80; 1 x 8 wavefronts, more LDS reads per MFMA, but e.g. 39 x 6
   // tiles fill one round where 33 x 6 leave 58 CUs idle) and 320x256 (1.25, fewer operand bytes per flop).
-  // The 160- and 320-row tiles read rows beyond M up to their own multiple, so they are used only where
+  // The 160-, 192- and 320-row tiles read rows beyond M up to their own multiple, so they are used only where
   // that stays inside the 256-row padding the caller guarantees.  Tiny problems take 128x128 tiles.
   const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
   const int64_t t192 = ((M + 191) / 192) * ((N + 255) / 256);
@@ -557,7 +557,8 @@ bool launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ld
   const int64_t t320 = ((M + 319) / 320) * ((N + 255) / 256);
   if (t256 < 64) { launch_cfg<128, 128, 2, 2>(A, lda, Wt, ldw, M, N, K, epi, e, st); return true; }
   const int64_t mpad = (M + 255) / 256 * 256;
-  const double cost256 = (double)((t256 + 255) / 256), cost192 = 0.88 * (double)((t192 + 255) / 256);
+  const double cost256 = (double)((t256 + 255) / 256);
+  const double cost192 = (M + 191) / 192 * 192 <= mpad ? 0.88 * (double)((t192 + 255) / 256) : 1e30;
   const double cost160 = (M + 159) / 160 * 160 <= mpad ? 0.80 * (double)((t160 + 255) / 256) : 1e30;
   const double cost320 = (M + 319) / 320 * 320 <= mpad ? 1.25 * (double)((t320 + 255) / 256) : 1e30;
   const double best = fmin(fmin(cost256, cost192), fmin(cost160, cost320));

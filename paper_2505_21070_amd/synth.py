@@ -38,6 +38,16 @@ CONFIGS = {
     # q|k|v projection, whose epilogue writes per head) and the attention kernel's 256-query blocks
     "wide128_bf16": dict(n_layers=1, dim=768, n_heads=6, head_dim=128, ffn_dim=1024, text_len=48, text_dim=768,
                          tok_h=16, tok_w=16, block_frames=8, cache_frames=2, dtype="bf16"),
+    # dim % 256 != 0, so q|k|v and the cross-attention query take the plain store epilogue and the separate
+    # norm / rotation / transpose kernels, at row counts that make the GEMM choose its other tile shapes for
+    # every epilogue: 4032 rows -> 192 x 256 tiles, 4096 rows -> 256 x 256, 4160 rows with dim 1408 -> 320 x 256
+    # (q|k|v) and 160 x 256 (the rest)
+    "tile192_bf16": dict(n_layers=1, dim=896, n_heads=7, head_dim=128, ffn_dim=1024, text_len=40, text_dim=896,
+                         tok_h=14, tok_w=36, block_frames=8, cache_frames=2, dtype="bf16"),
+    "tile256_bf16": dict(n_layers=1, dim=896, n_heads=7, head_dim=128, ffn_dim=1024, text_len=40, text_dim=896,
+                         tok_h=16, tok_w=32, block_frames=8, cache_frames=2, dtype="bf16"),
+    "tile320_bf16": dict(n_layers=1, dim=1408, n_heads=11, head_dim=128, ffn_dim=1024, text_len=40, text_dim=1408,
+                         tok_h=20, tok_w=26, block_frames=8, cache_frames=2, dtype="bf16"),
     # Wan-1.3B-shaped stage: 4 of 30 layers, 4 frames x 30x52 tokens + 2 cached frames
     "wan1p3b_stage": dict(n_layers=4, dim=1536, n_heads=12, head_dim=128, ffn_dim=8960, text_len=512,
                           text_dim=4096, tok_h=30, tok_w=52, block_frames=4, cache_frames=2, dtype="bf16"),

@@ -72,6 +72,16 @@ def test_small_bf16_stage(name, strong_gate):
     print({k: f"{v['rel_l2']:.2e}" for k, v in rep.items() if "cache" not in k})
 
 
+@pytest.mark.parametrize("name", ["tile192_bf16", "tile256_bf16", "tile320_bf16"])
+def test_every_gemm_tile_shape_and_epilogue(name):
+    """Row counts and widths at which the GEMM picks its 192-, 256-, 160- and 320-row tiles for the plain
+    store, GELU and residual epilogues (the other configurations only reach some of the combinations), with
+    dim % 256 != 0 so that q/k normalisation, rotation and the V transposition run as separate kernels."""
+    rep = {}
+    run_pair(name, 0, True, "later", rep)
+    print({k: f"{v['rel_l2']:.2e}" for k, v in rep.items() if "cache" not in k})
+
+
 @pytest.mark.parametrize("name", ["tiny", "small_bf16"])
 def test_cache_before_block_and_no_cache(name):
     run_pair(name, 1, True, "earlier")
