@@ -48,6 +48,12 @@ CONFIGS = {
                          tok_h=16, tok_w=32, block_frames=8, cache_frames=2, dtype="bf16"),
     "tile320_bf16": dict(n_layers=1, dim=1408, n_heads=11, head_dim=128, ffn_dim=1024, text_len=40, text_dim=1408,
                          tok_h=20, tok_w=26, block_frames=8, cache_frames=2, dtype="bf16"),
+    # few tokens, wide models: the widest register variants of the row kernels (LayerNorm, deferred key scale,
+    # norm + rotation); 6144 takes the per-head GEMM epilogue, 2176 = 17 x 128 the separate kernels
+    "dim6144_bf16": dict(n_layers=1, dim=6144, n_heads=48, head_dim=128, ffn_dim=512, text_len=24, text_dim=6144,
+                         tok_h=8, tok_w=8, block_frames=2, cache_frames=1, dtype="bf16"),
+    "dim2176_bf16": dict(n_layers=1, dim=2176, n_heads=17, head_dim=128, ffn_dim=640, text_len=24, text_dim=2176,
+                         tok_h=8, tok_w=8, block_frames=2, cache_frames=1, dtype="bf16"),
     # Wan-1.3B-shaped stage: 4 of 30 layers, 4 frames x 30x52 tokens + 2 cached frames
     "wan1p3b_stage": dict(n_layers=4, dim=1536, n_heads=12, head_dim=128, ffn_dim=8960, text_len=512,
                           text_dim=4096, tok_h=30, tok_w=52, block_frames=4, cache_frames=2, dtype="bf16"),

@@ -82,6 +82,15 @@ def test_every_gemm_tile_shape_and_epilogue(name):
     print({k: f"{v['rel_l2']:.2e}" for k, v in rep.items() if "cache" not in k})
 
 
+@pytest.mark.parametrize("name", ["dim6144_bf16", "dim2176_bf16"])
+def test_wide_and_odd_model_widths(name):
+    """Model widths that select the widest per-lane register variants of the row kernels, one with and one
+    without the per-head GEMM epilogue."""
+    rep = {}
+    run_pair(name, 0, True, "later", rep)
+    print({k: f"{v['rel_l2']:.2e}" for k, v in rep.items() if "cache" not in k})
+
+
 @pytest.mark.parametrize("name", ["tiny", "small_bf16"])
 def test_cache_before_block_and_no_cache(name):
     run_pair(name, 1, True, "earlier")
