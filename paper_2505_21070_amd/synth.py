@@ -26,6 +26,9 @@ CONFIGS = {
     # a small ragged bf16 case: head_dim 128, token counts that are not tile multiples, text MLP present
     "small_bf16": dict(n_layers=2, dim=256, n_heads=2, head_dim=128, ffn_dim=640, text_len=40, text_dim=192,
                        tok_h=6, tok_w=12, block_frames=3, cache_frames=2, dtype="bf16"),
+    # the same ragged shape in fp32, with odd token and text counts (7 x 9 tokens per frame, 37 text tokens)
+    "small_f32": dict(n_layers=2, dim=256, n_heads=2, head_dim=128, ffn_dim=640, text_len=37, text_dim=192,
+                      tok_h=7, tok_w=9, block_frames=3, cache_frames=2, dtype="f32"),
     # few queries against a long ragged key range (31.5 key tiles): the attention grid is small enough
     # that its work is cut into key ranges which a second kernel merges
     "longkv_bf16": dict(n_layers=1, dim=128, n_heads=2, head_dim=64, ffn_dim=256, text_len=24, text_dim=128,

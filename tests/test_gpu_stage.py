@@ -64,6 +64,16 @@ def test_tiny_fp32_stage(seed, strong_gate):
     print(f"tiny fp32 seed {seed} strong_gate {strong_gate}: worst max_abs {worst:.3e}")
 
 
+@pytest.mark.parametrize("strong_gate", [False, True])
+def test_ragged_fp32_stage(strong_gate):
+    """fp32 storage with head_dim 128 and token / text counts that are multiples of nothing (189-token
+    blocks, 126 cached, 37 text tokens, text MLP present)."""
+    rep = {}
+    run_pair("small_f32", 0, strong_gate, "later", rep)
+    worst = max(v["max_abs"] for v in rep.values())
+    print(f"small fp32 strong_gate {strong_gate}: worst max_abs {worst:.3e}")
+
+
 @pytest.mark.parametrize("name", ["tiny_bf16", "small_bf16", "longkv_bf16", "wide64_bf16", "wide128_bf16"])
 @pytest.mark.parametrize("strong_gate", [False, True])
 def test_small_bf16_stage(name, strong_gate):
