@@ -164,13 +164,15 @@ typedef struct {
  * for DP_ORDER_REVERSE), each pass lowers the block's level by one, and a block leaves after its
  * level-1 pass.  There are T * block_num passes.  *n_written receives the number of passes; if
  * capacity is smaller the call writes nothing and returns DP_ENOMEM (out may then be NULL).
- * Errors: DP_EINVAL (null cfg / n_written, non-positive sizes), DP_ENOMEM.
+ * Errors: DP_EINVAL (null cfg / n_written, non-positive sizes, frame indices or step numbers beyond
+ * 2^31 - 1), DP_ENOMEM.
  */
 int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry* out, int64_t capacity,
                           int64_t* n_written);
 
 /* Bubble ratio of the device pipeline as the paper prints it: Eq. 3 / Eq. 4 for DP_ORDER_REVERSE
- * (N <= block_num / N > block_num), Eq. 5 for DP_ORDER_SEQUENTIAL.  Host only.  Returns -1 on bad input. */
+ * (N <= block_num / N > block_num), Eq. 5 for DP_ORDER_SEQUENTIAL.  Host only.  Returns -1 on bad input
+ * (a size below 1, an unknown order, or sizes at which the printed form has no positive denominator). */
 double dp_bubble_ratio(int32_t n_devices, int32_t T, int32_t block_num, int32_t order);
 
 /* Slot-level count of the device pipeline that runs the block queue (Sec. 3.1, 3.4, appendix on the denoising
@@ -181,7 +183,8 @@ double dp_bubble_ratio(int32_t n_devices, int32_t T, int32_t block_num, int32_t 
  *   bubble_per_device : out, makespan - T * block_num, the idle slots of each device
  * For T > N and block_num >= 2 the count equals the numerators of Eq. 5 and Eq. 4, and (N-1)^2 for the
  * tail-to-head order with N <= block_num (Eq. 3 prints N^2-N-1; dp_bubble_ratio returns the printed forms).
- * Errors: DP_EINVAL (null pointer, non-positive size, unknown order). */
+ * Errors: DP_EINVAL (null pointer, non-positive size, unknown order, more than 2^34 (pass, device) slots to
+ * count), DP_ENOMEM (host memory). */
 int dp_pipeline_simulate(int32_t n_devices, int32_t T, int32_t block_num, int32_t order, int64_t* makespan,
                          int64_t* bubble_per_device);
 
@@ -198,7 +201,8 @@ int dp_pipeline_simulate(int32_t n_devices, int32_t T, int32_t block_num, int32_
  *   random_words : host, at least (block_num - 1) * (num_b - 1) words (may be NULL if that is 0)
  *   pool_index   : host, out; *n_written receives the number of entries.  capacity too small: nothing
  *                  is written, DP_ENOMEM (pool_index may then be NULL)
- * Errors: DP_EINVAL (null cfg / n_written, block_num < 1, num_b < 1, num_c < 0, too few words), DP_ENOMEM.
+ * Errors: DP_EINVAL (null cfg / n_written, block_num < 1, num_b < 1, num_c < 0, too few words, a pool beyond
+ * 2^31 - 1 frames), DP_ENOMEM.
  *
  * dp_noise_gather (device) materialises a block's initial noise: out[f, :] = pool[index[f], :].
  *   pool        : device, [pool_frames, frame_bytes] bytes, 16-byte aligned; frame_bytes % 16 == 0

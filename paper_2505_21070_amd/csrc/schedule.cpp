@@ -1,4 +1,6 @@
 // Host-side queue schedule of block-wise denoising and the paper's bubble-ratio closed forms.
+#include <climits>
+#include <new>
 #include <vector>
 
 #include "../../include/dualparal.h"
@@ -19,6 +21,11 @@ extern "C" int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry*
     return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: unknown order");
   if (cfg->input != DP_INPUT_BLOCK && cfg->input != DP_INPUT_EXTENDED && cfg->input != DP_INPUT_NOCACHE)
     return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: unknown input variant");
+  // frame indices and step numbers are 32-bit fields of dp_sched_entry
+  const int64_t first64 = cfg->first_block_frames > 0 ? cfg->first_block_frames : cfg->num_b;
+  if (first64 + (int64_t)(cfg->block_num - 1) * cfg->num_b + cfg->num_c / 2 > INT32_MAX ||
+      (int64_t)cfg->T + cfg->block_num - 1 > INT32_MAX)
+    return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: frame or step count beyond 2^31 - 1");
   const int64_t total = (int64_t)cfg->T * cfg->block_num;
   *n_written = total;
   if (capacity < total || !out) return dp_set_error(DP_ENOMEM, "dp_blockwise_schedule: capacity too small");
@@ -67,7 +74,8 @@ extern "C" double dp_bubble_ratio(int32_t N, int32_t T, int32_t block_num, int32
   else if (order != DP_ORDER_REVERSE) return -1.0;
   else if (N <= block_num) bubble = (double)N * N - N - 1.0;
   else bubble = (double)block_num * (N - T) + (double)N * (T - 2) + 1.0;
-  return bubble / (bubble + (double)T * block_num);
+  const double all = bubble + (double)T * block_num;
+  return all > 0.0 ? bubble / all : -1.0;               // N = T = block_num = 1 is outside the printed forms
 }
 
 // Sec. 3.4 / appendix: in-order pipeline of N one-slot stages fed by the queue schedule; a block's next pass waits
@@ -78,10 +86,19 @@ extern "C" int dp_pipeline_simulate(int32_t N, int32_t T, int32_t block_num, int
   if (N < 1 || T < 1 || block_num < 1) return dp_set_error(DP_EINVAL, "dp_pipeline_simulate: non-positive size");
   if (order != DP_ORDER_REVERSE && order != DP_ORDER_SEQUENTIAL)
     return dp_set_error(DP_EINVAL, "dp_pipeline_simulate: unknown order");
-  std::vector<int64_t> free_at((size_t)N, 0), done((size_t)block_num + 1, 0);
-  for (int32_t step = 1; step <= T + block_num - 1; ++step) {
-    int32_t lo = step - T + 1; if (lo < 1) lo = 1;
-    const int32_t hi = step < block_num ? step : block_num;
+  // the count visits every (pass, device) pair once; beyond 2^34 visits it is refused rather than left running
+  if ((double)N * (double)T * (double)block_num > 17179869184.0)
+    return dp_set_error(DP_EINVAL, "dp_pipeline_simulate: more than 2^34 device slots to count");
+  std::vector<int64_t> free_at, done;
+  try {
+    free_at.assign((size_t)N, 0);
+    done.assign((size_t)block_num + 1, 0);
+  } catch (const std::bad_alloc&) {
+    return dp_set_error(DP_ENOMEM, "dp_pipeline_simulate: out of host memory");
+  }
+  for (int64_t step = 1; step <= (int64_t)T + block_num - 1; ++step) {
+    int32_t lo = (int32_t)(step - T + 1 < 1 ? 1 : step - T + 1);
+    const int32_t hi = (int32_t)(step < block_num ? step : block_num);
     for (int32_t i = 0; i <= hi - lo; ++i) {
       const int32_t b = order == DP_ORDER_REVERSE ? hi - i : lo + i;
       int64_t t = done[(size_t)b];
@@ -105,6 +122,8 @@ extern "C" int dp_noise_assign(const dp_noise_config* cfg, const uint32_t* rando
   if (!cfg || !n_written) return dp_set_error(DP_EINVAL, "dp_noise_assign: null pointer");
   if (cfg->block_num < 1 || cfg->num_b < 1 || cfg->num_c < 0)
     return dp_set_error(DP_EINVAL, "dp_noise_assign: bad block_num / num_b / num_c");
+  if ((int64_t)cfg->num_b + cfg->num_c / 2 > INT32_MAX)
+    return dp_set_error(DP_EINVAL, "dp_noise_assign: pool beyond 2^31 - 1 frames");
   const int32_t nb = cfg->num_b, half = cfg->num_c / 2, pool = nb + half;
   const int64_t need_words = (int64_t)(cfg->block_num - 1) * (nb - 1);
   if (n_words < need_words || (need_words > 0 && !random_words))
