@@ -75,7 +75,10 @@ typedef struct {
   const dp_layer_weights* layers; /* host array of n_layers entries                               */
 } dp_stage_weights;
 
-/* Bytes of device workspace a stage of this geometry needs (0 if the config is invalid). */
+/* Bytes of device workspace a stage of this geometry needs (0 if the config is invalid; dp_last_error says
+ * why).  Limits besides those stated at the fields: dim <= 8192, n_layers <= 1024, ffn_dim <= 2^17,
+ * text_dim <= 2^16, text_len <= 2^20, freq_dim <= 2^16, max_abs_frames <= 2^24, and at most 2^24 tokens
+ * (tok_h * tok_w * frames) in a block and in the cache. */
 size_t dp_stage_workspace_bytes(const dp_stage_config* cfg);
 
 /*
@@ -255,6 +258,7 @@ typedef struct {              /* device pointers, matrices row-major [in, out], 
   const void *w_head, *b_head;/* [dim, 4*channels], [4*channels]                                     */
   const void *wt1, *bt1, *wt2, *bt2; /* timestep MLP, the same arrays the stages use                 */
 } dp_ends_weights;
+/* 0 if the config is invalid (dim <= 8192, channels and freq_dim <= 2^16, at most 2^24 tokens). */
 size_t dp_ends_workspace_bytes(const dp_ends_config* cfg);
 int dp_ends_init(const dp_ends_config* cfg, const dp_ends_weights* weights, void* workspace,
                  size_t workspace_bytes, void* hip_stream, dp_ends_t** out);

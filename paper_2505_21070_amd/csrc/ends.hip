@@ -57,6 +57,10 @@ static const char* validate(const dp_ends_config* c) {
   if (c->freq_dim < 2 || (c->freq_dim & 1)) return "freq_dim must be even";
   if (!(c->eps >= 0.f)) return "bad eps";
   if (c->dim % 8 || c->dim > 8192) return "dim must be a multiple of 8 and at most 8192";
+  // upper limits far beyond any model, so that no size below can overflow
+  if (c->channels > (1 << 16) || c->freq_dim > (1 << 16) || (int64_t)c->tok_h * c->tok_w > (1 << 24) ||
+      (int64_t)c->tok_h * c->tok_w * c->max_frames > (1 << 24))
+    return "channels / freq_dim beyond 2^16 or more than 2^24 tokens";
   if (c->dtype == DP_BF16 && (c->dim % 64 || (4 * c->channels) % 64)) return "bf16 path needs dim and 4*channels % 64 == 0";
   return nullptr;
 }

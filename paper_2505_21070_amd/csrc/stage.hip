@@ -114,6 +114,14 @@ static const char* validate(const dp_stage_config* c) {
   if (c->dtype != DP_F32 && c->dtype != DP_BF16) return "dtype must be DP_F32 or DP_BF16";
   if (c->freq_dim < 2 || (c->freq_dim & 1)) return "freq_dim must be even";
   if (!(c->rope_theta > 0.f) || !(c->eps >= 0.f)) return "bad rope_theta / eps";
+  // Upper limits far beyond any model, so that no size below can overflow 64 bits or a 32-bit grid:
+  // 2^24 tokens per block and in the cache, 2^24 frame positions, 2^20 text tokens
+  if (c->n_layers > 1024 || c->ffn_dim > (1 << 17) || c->text_dim > (1 << 16) || c->text_len > (1 << 20) ||
+      c->freq_dim > (1 << 16) || c->max_abs_frames > (1 << 24))
+    return "n_layers / ffn_dim / text_dim / text_len / freq_dim / max_abs_frames beyond the supported range";
+  if ((int64_t)c->tok_h * c->tok_w > (1 << 24) || (int64_t)c->tok_h * c->tok_w * c->max_block_frames > (1 << 24) ||
+      (int64_t)c->tok_h * c->tok_w * c->max_cache_frames > (1 << 24))
+    return "more than 2^24 tokens in a block or in the cache";
   {
     const int64_t spad = rup((int64_t)c->tok_h * c->tok_w * c->max_block_frames, 256);
     if (rup(c->text_len, 256) > 3 * spad) return "text_len too large for the block size";
@@ -204,8 +212,13 @@ static size_t zero_span(dp_stage* s) {   // bytes from the workspace start that 
 extern "C" size_t dp_stage_workspace_bytes(const dp_stage_config* cfg) {
   const char* why = validate(cfg);
   if (why) { fail(DP_EINVAL, "dp_stage_workspace_bytes: %s", why); return 0; }
-  dp_stage tmp; tmp.cfg = *cfg;
-  return carve(&tmp, nullptr);
+  try {
+    dp_stage tmp; tmp.cfg = *cfg;
+    return carve(&tmp, nullptr);
+  } catch (const std::bad_alloc&) {
+    fail(DP_ENOMEM, "dp_stage_workspace_bytes: out of host memory");
+    return 0;
+  }
 }
 
 // ------------------------------------------------------------------------------------------ typed helpers
@@ -323,9 +336,15 @@ extern "C" int dp_stage_init(const dp_stage_config* cfg, const dp_stage_weights*
   dp_stage* s = new (std::nothrow) dp_stage();
   if (!s) return fail(DP_ENOMEM, "dp_stage_init: host allocation failed");
   s->cfg = *cfg; s->w = *weights;
-  s->lw.assign(weights->layers, weights->layers + cfg->n_layers);
-  s->w.layers = s->lw.data();
-  const size_t need = carve(s, nullptr);
+  size_t need = 0;
+  try {
+    s->lw.assign(weights->layers, weights->layers + cfg->n_layers);
+    s->w.layers = s->lw.data();
+    need = carve(s, nullptr);
+  } catch (const std::bad_alloc&) {
+    delete s;
+    return fail(DP_ENOMEM, "dp_stage_init: host allocation failed");
+  }
   if (workspace_bytes < need) {
     delete s;
     return fail(DP_ENOMEM, "dp_stage_init: workspace has %zu bytes, %zu needed", workspace_bytes, need);
@@ -545,7 +564,8 @@ extern "C" int dp_stage_profile_begin(dp_stage_t* s, uint32_t class_mask) {
   if (!s) return fail(DP_EINVAL, "dp_stage_profile_begin: null stage");
   Profiler& p = s->prof;
   if (class_mask && p.ev.empty()) {
-    p.ev.resize(2 * 16384);
+    try { p.ev.resize(2 * 16384); p.cls.reserve(16384); }
+    catch (const std::bad_alloc&) { p.ev.clear(); return fail(DP_ENOMEM, "dp_stage_profile_begin: host allocation failed"); }
     for (size_t i = 0; i < p.ev.size(); ++i) {
       if (hipEventCreate(&p.ev[i]) != hipSuccess) {
         for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(p.ev[j]);
