@@ -463,7 +463,7 @@ extern "C" int dp_stage_forward(dp_stage_t* s, const void* x_in, void* x_out, in
   if (n_frames < 1 || n_frames > s->cfg.max_block_frames)
     return fail(DP_EINVAL, "dp_stage_forward: n_frames %d outside [1, %d]", n_frames, s->cfg.max_block_frames);
   if (frame0 < 0 || (int64_t)frame0 + n_frames > s->cfg.max_abs_frames)
-    return fail(DP_EINVAL, "dp_stage_forward: frames [%d, %d) outside [0, %d)", frame0, frame0 + n_frames, s->cfg.max_abs_frames);
+    return fail(DP_EINVAL, "dp_stage_forward: frames [%d, %lld) outside [0, %d)", frame0, (long long)frame0 + n_frames, s->cfg.max_abs_frames);
   if (!(timestep == timestep)) return fail(DP_EINVAL, "dp_stage_forward: timestep is NaN");
   hipStream_t st = (hipStream_t)hip_stream;
   (void)hipGetLastError();
@@ -484,9 +484,9 @@ extern "C" int dp_cache_update(dp_stage_t* s, int32_t first_frame, int32_t n_fra
   if (s->last_frames == 0) return fail(DP_ESTATE, "dp_cache_update: no block has been processed yet");
   if (n_frames < 0 || n_frames > s->cfg.max_cache_frames)
     return fail(DP_EINVAL, "dp_cache_update: n_frames %d outside [0, %d]", n_frames, s->cfg.max_cache_frames);
-  if (first_frame < 0 || first_frame + n_frames > s->last_frames)
-    return fail(DP_EINVAL, "dp_cache_update: frames [%d, %d) outside the last block's %d frames", first_frame,
-                first_frame + n_frames, s->last_frames);
+  if (first_frame < 0 || (int64_t)first_frame + n_frames > s->last_frames)
+    return fail(DP_EINVAL, "dp_cache_update: frames [%d, %lld) outside the last block's %d frames", first_frame,
+                (long long)first_frame + n_frames, s->last_frames);
   // nothing is copied: the frames stay where the last forward wrote them and the next block goes around them
   (void)hip_stream;
   s->cache0 = s->blk0 + s->tok * first_frame;

@@ -246,6 +246,16 @@ def test_error_paths_leave_gpu_alone():
     with pytest.raises(B.DualParalError) as ei:
         g.cache_update(1, 2)                      # beyond the last block / above max_cache_frames
     assert ei.value.code == B.DP_EINVAL
+    for first, n in ((2 ** 31 - 1, 1), (2 ** 31 - 1, 2 ** 31 - 1), (-1, 1), (0, -1)):   # sums past 32 bits, negatives
+        with pytest.raises(B.DualParalError) as ei:
+            g.cache_update(first, n)
+        assert ei.value.code == B.DP_EINVAL
+    for f0, nfr in ((2 ** 31 - 1, 2), (-1, 2), (0, 0), (0, -2 ** 31)):
+        with pytest.raises(B.DualParalError) as ei:
+            B._check(B._lib.dp_stage_forward(g._h, x.data_ptr(), x.data_ptr(), nfr, f0, 1.0, None), "dp_stage_forward")
+        assert ei.value.code == B.DP_EINVAL
+    y = g.forward(x, 2, 0, 1.0)                   # and the stage still works
+    assert torch.isfinite(y.float()).all()
     conf = B.make_config(cfg)
     ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
     h = B.C.c_void_p()
