@@ -108,6 +108,10 @@ int dp_stage_init(const dp_stage_config* cfg, const dp_stage_weights* weights, c
  *   n_frames in [1, max_block_frames]; frame0 >= 0 is the absolute index of the block's first frame,
  *   frame0 + n_frames <= max_abs_frames; timestep is the block's noise level on the model's
  *   timestep scale (e.g. 0..1000).
+ * Asynchronous on hip_stream.  The call allocates nothing, waits for nothing and issues only kernel
+ * launches, so it may be recorded into a HIP graph (after one ordinary call, which sets the kernels'
+ * attributes); a replay repeats the launch with the pointers, block position and cache range of the
+ * moment of capture and does not advance the handle's host-side state.
  * Errors: DP_EINVAL (bad sizes / null), DP_EHIP.
  */
 int dp_stage_forward(dp_stage_t* stage, const void* x_in, void* x_out, int32_t n_frames,
