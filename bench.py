@@ -289,6 +289,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the stage has no CPU path", file=sys.stderr)
         sys.exit(3)
+    from paper_2505_21070_amd import build as lib_build
+    lib_build.ensure_built()                # loads what is built; builds only if nothing is
     if args.workload == "wan1p3b_ablation":
         return cache_ablation(args)
     if args.workload == "wan1p3b_latent":

@@ -35,5 +35,11 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """For the scripts around the library (tests, bench, smoke): builds only if no library is there.  The
+    binding never calls this; without a library it raises."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
