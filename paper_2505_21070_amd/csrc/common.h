@@ -104,7 +104,8 @@ struct HeadsArgs {
 };
 
 struct EpiArgs {
-  void* out;            // EPI_STORE / EPI_GELU: [M, ldo] of the activation type
+  void* out;            // EPI_STORE / EPI_GELU: [M, ldo] of the activation type; EPI_RESID (bf16 GEMM): optional
+                        // copy of the updated residual rows, rounded to bf16 (null = none)
   int64_t ldo;
   const void* bias;     // [N] of the weight type, may be null
   float* resid;         // EPI_RESID: fp32 [M, ldr], updated in place: resid += gate * (acc + bias)

@@ -79,22 +79,34 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t st) {   // bytes % 4 ==
 // ---------------------------------------------------------------- LayerNorm + modulate
 // One wavefront per row; the row lives in registers (NCH float4 per lane), so x is read once.
 // Two-pass statistics (mean, then centred variance) in fp32.
+// xin != null: the row is read from xin (bf16) instead of x, and x receives its fp32 copy (the first
+// LayerNorm of a stage, which thereby also fills the fp32 residual stream).
 template <typename T, int NCH>
-__global__ __launch_bounds__(256) void k_ln_modulate(const float* __restrict__ x, T* __restrict__ out,
-                                                     int64_t S, int D, float eps,
+__global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, const bf16_t* __restrict__ xin,
+                                                     T* __restrict__ out, int64_t S, int D, float eps,
                                                      const float* __restrict__ mul,
                                                      const float* __restrict__ add, float plus) {
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= S) return;
-  const float4* xr = (const float4*)(x + row * D);
+  float4* xr = (float4*)(x + row * D);
   const int nvec = D >> 2;
   float4 v[NCH];
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
     const int idx = i * 64 + lane;
-    if (idx < nvec) { v[i] = xr[idx]; sum += (v[i].x + v[i].y) + (v[i].z + v[i].w); }
+    if (idx < nvec) {
+      if (xin) {
+        const uint2 w = ((const uint2*)(xin + row * D))[idx];
+        v[i] = make_float4(bf16_to_f32((bf16_t)(w.x & 0xffff)), bf16_to_f32((bf16_t)(w.x >> 16)),
+                           bf16_to_f32((bf16_t)(w.y & 0xffff)), bf16_to_f32((bf16_t)(w.y >> 16)));
+        xr[idx] = v[i];
+      } else {
+        v[i] = xr[idx];
+      }
+      sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
     else v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
   const float mean = wave_sum(sum) / (float)D;
@@ -129,17 +141,17 @@ __global__ __launch_bounds__(256) void k_ln_modulate(const float* __restrict__ x
   }
 }
 template <typename T>
-void launch_ln_modulate(const float* x, T* out, int64_t S, int D, float eps, const float* mul,
+void launch_ln_modulate(float* x, const bf16_t* xin, T* out, int64_t S, int D, float eps, const float* mul,
                         const float* add, int plus_one, hipStream_t st) {
   const int grid = cdiv(S, 4);
   const float plus = plus_one ? 1.f : 0.f;
-  if (D <= 256) k_ln_modulate<T, 1><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);
-  else if (D <= 2048) k_ln_modulate<T, 8><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);
-  else if (D <= 5120) k_ln_modulate<T, 20><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);
-  else k_ln_modulate<T, 32><<<grid, 256, 0, st>>>(x, out, S, D, eps, mul, add, plus);   // D <= 8192
+  if (D <= 256) k_ln_modulate<T, 1><<<grid, 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus);
+  else if (D <= 2048) k_ln_modulate<T, 8><<<grid, 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus);
+  else if (D <= 5120) k_ln_modulate<T, 20><<<grid, 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus);
+  else k_ln_modulate<T, 32><<<grid, 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus);   // D <= 8192
 }
-template void launch_ln_modulate<float>(const float*, float*, int64_t, int, float, const float*, const float*, int, hipStream_t);
-template void launch_ln_modulate<bf16_t>(const float*, bf16_t*, int64_t, int, float, const float*, const float*, int, hipStream_t);
+template void launch_ln_modulate<float>(float*, const bf16_t*, float*, int64_t, int, float, const float*, const float*, int, hipStream_t);
+template void launch_ln_modulate<bf16_t>(float*, const bf16_t*, bf16_t*, int64_t, int, float, const float*, const float*, int, hipStream_t);
 
 // ---------------------------------------------------------------- RMSNorm over D + 3D RoPE, head-major output
 // One wavefront per token and job (blockIdx.y: e.g. q and k of the same row), four tokens per block.  A lane

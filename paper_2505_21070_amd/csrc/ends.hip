@@ -164,7 +164,7 @@ static void head_typed(dp_ends* s, const void* x_in, float t, float* v_out, int 
   launch_gemv<T>(s->e1, gemv_slices(c.freq_dim, (int)D), (int)D, (const T*)s->w.bt1, (int)D, (const T*)s->w.wt2, (int)D, 1, s->e, st);
   launch_mod_add<T>(s->mhead, s->e, gemv_slices((int)D, (int)D), (const T*)s->w.bt2, s->mod, 2, (int)D, st);   // rows: shift, scale
   launch_to_f32<T>((const T*)x_in, s->x32, S * D, st);
-  launch_ln_modulate<T>(s->x32, (T*)s->h, S, (int)D, c.eps, s->mod + D, s->mod, 1, st);
+  launch_ln_modulate<T>(s->x32, nullptr, (T*)s->h, S, (int)D, c.eps, s->mod + D, s->mod, 1, st);
   // fp32 output through the residual epilogue (out32 += h W + b) on a cleared buffer
   launch_fill_zero(s->out32, (size_t)n * 4, st);
   gemm<T>(s, s->h, D, s->w.w_head, s->w_head_t, S, s->P, D, EPI_RESID, EpiArgs{nullptr, 0, s->w.b_head, s->out32, s->P, nullptr}, st);

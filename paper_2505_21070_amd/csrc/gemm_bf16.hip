@@ -482,6 +482,12 @@ __global__ __launch_bounds__(WGM * WGN * 64) void k_gemm_bf16(const bf16_t* __re
             float4 xv = *x;
             xv.x += v.x; xv.y += v.y; xv.z += v.z; xv.w += v.w;
             *x = xv;
+            if (e.out) {             // the stage's last GEMM: the block's output in the storage type, same rows
+              uint2 pk;
+              pk.x = cvt_pk_bf16(xv.x, xv.y);
+              pk.y = cvt_pk_bf16(xv.z, xv.w);
+              *(uint2*)((bf16_t*)e.out + m * e.ldo + n) = pk;
+            }
           }
         }
       }

@@ -6,9 +6,10 @@
 // ---- elementwise.hip -------------------------------------------------------------------------
 template <typename T> void launch_to_f32(const T* in, float* out, int64_t n, hipStream_t st);
 template <typename T> void launch_from_f32(const float* in, T* out, int64_t n, hipStream_t st);
-// out[s,:] = LayerNorm(x[s,:]) * (mul + plus_one) + add ; x fp32 [S,D], mul/add fp32 [D]
+// out[s,:] = LayerNorm(x[s,:]) * (mul + plus_one) + add ; x fp32 [S,D], mul/add fp32 [D].
+// xin != null: the rows are read from xin (bf16 [S,D]) instead, and x receives their fp32 copy.
 template <typename T>
-void launch_ln_modulate(const float* x, T* out, int64_t S, int D, float eps, const float* mul,
+void launch_ln_modulate(float* x, const bf16_t* xin, T* out, int64_t S, int D, float eps, const float* mul,
                         const float* add, int plus_one, hipStream_t st);
 
 // src[S, ld] holds un-normalised projections; job j takes columns [col, col+D) of every row:

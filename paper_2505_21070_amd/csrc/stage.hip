@@ -368,7 +368,9 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
   const int64_t D = c.dim, F = c.ffn_dim, S = s->tok * n_frames;
   const int h = c.n_heads, d = c.head_dim;
   constexpr bool bf = sizeof(T) == 2;
-  PROF(DP_PROF_CONVERT, launch_to_f32<T>((const T*)x_in, s->xres, S * D, st));
+  // bf16 storage: the first LayerNorm reads x_in itself and leaves its fp32 copy in the residual stream, and
+  // the last GEMM writes x_out next to its residual update, so neither end needs a conversion pass
+  if (!bf) PROF(DP_PROF_CONVERT, launch_to_f32<T>((const T*)x_in, s->xres, S * D, st));
   // adaLN modulation: sinusoidal features -> two-layer MLP (SiLU) -> SiLU -> 6*dim head, plus each layer's table
   PROF(DP_PROF_MODULATION,
        launch_sinusoid(t, c.freq_dim, s->tau, st);
@@ -391,7 +393,8 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
     const float* md = s->mod + (int64_t)l * 6 * D;
     const float *sh1 = md, *sc1 = md + D, *g1 = md + 2 * D, *sh2 = md + 3 * D, *sc2 = md + 4 * D, *g2 = md + 5 * D;
     // --- self-attention over [cached K/V ; this block]
-    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, sc1, sh1, 1, st));
+    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, bf && l == 0 ? (const bf16_t*)x_in : nullptr, (T*)s->hbuf, S, (int)D,
+                                           c.eps, sc1, sh1, 1, st));
     AttnQNorm qn{s->qssq, 0, s->Smax, 1.f / (float)D, c.eps, Path<T>::q_scale(d)};
     if (s->heads_epi) {
       HeadsArgs ha{};
@@ -427,7 +430,7 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
     PROF(DP_PROF_OPROJ_GEMM, Path<T>::gemm(s->attn_o, D, w.wo, m.wo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.bo, g1), st));
     if (s->tap_xself && l == c.n_layers - 1) launch_copy2d<float>(s->xres, 0, s->tap_xself, 0, 1, S * D, st);
     // --- cross-attention to the text tokens
-    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, m.ln3g, m.ln3b, 0, st));
+    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, nullptr, (T*)s->hbuf, S, (int)D, c.eps, m.ln3g, m.ln3b, 0, st));
     if (s->heads_epi) {
       HeadsArgs ha{};
       ha.dim = (int)D; ha.head_dim = d; ha.ssq_stride = s->Smax;
@@ -450,11 +453,13 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
     PROF(DP_PROF_CROSS_O_GEMM, Path<T>::gemm(s->attn_o, D, w.cwo, m.cwo_t, S, D, D, EPI_RESID, epi_resid(s->xres, D, w.cbo, nullptr), st));
     if (s->tap_xcross && l == c.n_layers - 1) launch_copy2d<float>(s->xres, 0, s->tap_xcross, 0, 1, S * D, st);
     // --- FFN
-    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, (T*)s->hbuf, S, (int)D, c.eps, sc2, sh2, 1, st));
+    PROF(DP_PROF_LN, launch_ln_modulate<T>(s->xres, nullptr, (T*)s->hbuf, S, (int)D, c.eps, sc2, sh2, 1, st));
     PROF(DP_PROF_FFN1_GEMM, Path<T>::gemm(s->hbuf, D, w.w1, m.w1_t, S, F, D, EPI_GELU, epi_store(s->mid, F, w.b1), st));
-    PROF(DP_PROF_FFN2_GEMM, Path<T>::gemm(s->mid, F, w.w2, m.w2_t, S, D, F, EPI_RESID, epi_resid(s->xres, D, w.b2, g2), st));
+    EpiArgs e2 = epi_resid(s->xres, D, w.b2, g2);
+    if (bf && l == c.n_layers - 1) { e2.out = x_out; e2.ldo = D; }
+    PROF(DP_PROF_FFN2_GEMM, Path<T>::gemm(s->mid, F, w.w2, m.w2_t, S, D, F, EPI_RESID, e2, st));
   }
-  PROF(DP_PROF_CONVERT, launch_from_f32<T>(s->xres, (T*)x_out, S * D, st));
+  if (!bf) PROF(DP_PROF_CONVERT, launch_from_f32<T>(s->xres, (T*)x_out, S * D, st));
 }
 
 extern "C" int dp_stage_forward(dp_stage_t* s, const void* x_in, void* x_out, int32_t n_frames, int32_t frame0,
