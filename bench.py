@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0         # HBM3E, published
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for a plain streaming copy of known
 # size (the stage's fp32 -> bf16 output conversion); figures and commands in
 # profiles/bench_wan1p3b_stage.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 224.8e6}
+MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 224.0e6}
 
 
 def class_work(cfg, S, Nc):
