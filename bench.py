@@ -24,7 +24,7 @@ PEAK_HBM_GBS = 8000.0         # HBM3E, published
 
 # HBM-side bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this command
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for a plain streaming copy of known
-# size (the stage's fp32 -> bf16 output conversion); figures and commands in
+# size (the LayerNorm dispatches that read the fp32 residual stream); figures and commands in
 # profiles/bench_wan1p3b_stage.md.  None where not measured.
 MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 224.0e6}
 
