@@ -22,11 +22,27 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
 PEAK_FP32_TFLOPS = 157.3      # fp32 vector
 PEAK_HBM_GBS = 8000.0         # HBM3E, published
 
-# HBM-side bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this command
-# (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for a plain streaming copy of known
-# size (the LayerNorm dispatches that read the fp32 residual stream); figures and commands in
-# profiles/bench_wan1p3b_stage.md.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {("wan1p3b_stage", "self_attn"): 224.0e6}
+# HBM-side bytes per launch of the dominant kernel from two `rocprofv3 --pmc` runs of this command (FETCH_SIZE,
+# then WRITE_SIZE, each scaled by what the same counter reads for the LayerNorm dispatches, streaming kernels of
+# known size); figures and commands in profiles/bench_<workload>.md.  An entry is only valid for the kernel source
+# it was measured on: `src` names the source file and `sha` the first 16 hex digits of its SHA-256 at the time of
+# the profile.  With any other source (or no entry) the bench prints null instead of a stale figure.
+MEASURED_TRAFFIC = {
+}
+
+
+def measured_traffic(workload, kernel):
+    import hashlib
+    ent = MEASURED_TRAFFIC.get((workload, kernel))
+    if not ent:
+        return None
+    path = os.path.join(ROOT, "paper_2505_21070_amd", "csrc", ent["src"])
+    try:
+        with open(path, "rb") as f:
+            sha = hashlib.sha256(f.read()).hexdigest()[:16]
+    except OSError:
+        return None
+    return ent["bytes"] if sha == ent["sha"] else None
 
 
 def class_work(cfg, S, Nc):
@@ -48,53 +64,53 @@ def class_work(cfg, S, Nc):
     }
 
 
-def cpu_baseline(cfg, weights, text, x_block, n_rows=96, budget_s=12.0):
-    """The CPU oracle timed on a bounded sample of the same workload: layer 0 of the stage on one block,
-    keys/values for every token of the block (and a synthetic cache of the workload's size), the rest of
-    the layer for sampled query rows; extrapolated to all rows and all layers.  A first batch of `n_rows`
-    rows gives the cost per row, a second batch is sized so that the whole sample takes about `budget_s`."""
+def cpu_baseline(cfg, weights, text, x_block, budget_s=24.0):
+    """The CPU oracle (its fp32 build, the plain fp32 CPU implementation) timed on a bounded sample of the same
+    workload: layer 0 of the stage; keys/values for `n_kv` of the block's S tokens, the rest of the layer for
+    `n_rows` sampled query rows, each attending over S + Nc keys (the keys the sample did not compute are
+    synthetic, like the cache).  A small calibration run gives the oracle's rate on this host, which sizes the
+    sample to the time budget; the sample's time is scaled to the whole step by algorithmic flops (keys/values
+    for S tokens + the rest of the layer for S rows, times the number of layers)."""
     import numpy as np
     from oracle.stage import OracleStage, token_positions
-    from paper_2505_21070_amd import synth
+    cores = int(os.environ.get("OMP_NUM_THREADS") or os.cpu_count())
     one = dict(cfg, n_layers=1)
-    wn = synth.to_numpy(weights)
+    host = {"stage": {k: v.numpy() for k, v in weights["stage"].items()},
+            "layers": [{k: v.numpy() for k, v in weights["layers"][0].items()}]}
     t0 = time.perf_counter()
-    st = OracleStage(one, {"stage": wn["stage"], "layers": wn["layers"][:1]}, text.numpy())
+    st = OracleStage(one, host, text.numpy(), real="f32")
     t_init = time.perf_counter() - t0
-    nf, tok = cfg["block_frames"], cfg["tok_h"] * cfg["tok_w"]
+    nf, tok, D, F, Lt = cfg["block_frames"], cfg["tok_h"] * cfg["tok_w"], cfg["dim"], cfg["ffn_dim"], cfg["text_len"]
     S, Nc = nf * tok, cfg["cache_frames"] * tok
-    x = x_block.numpy().astype(np.float64)
+    f_kv = 2.0 * D * 2 * D                                             # K and V projections of one token
+    f_row = 2.0 * D * 4 * D + 4.0 * (S + Nc) * D + 4.0 * Lt * D + 4.0 * D * F   # q, o, cross q, cross o; attention; FFN
+    x = x_block.numpy()
     e0 = st.modulation(500.0)
     pos = token_positions(nf, 0, cfg["tok_h"], cfg["tok_w"])
-    rng = np.random.default_rng(0)
-    cache = (rng.standard_normal((Nc, cfg["dim"])), rng.standard_normal((Nc, cfg["dim"])))
-    order = rng.permutation(S)
-    # keys/values of every token: time them alone by asking for one query row ...
-    t0 = time.perf_counter()
-    st.layer(0, x, e0, pos, cache, rows=np.sort(order[:1]))
-    t_kv1 = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    st.layer(0, x, e0, pos, cache, rows=np.sort(order[:n_rows]))
-    t_a = time.perf_counter() - t0
-    per_row = max(t_a - t_kv1, 1e-9) / (n_rows - 1)
-    measured, rows_done = t_kv1 + t_a, n_rows
-    extra = int(min(S - n_rows, (budget_s - measured - t_kv1) / per_row)) if per_row > 0 else 0
-    if extra > n_rows:
+    base = np.random.default_rng(0).standard_normal((1024, D)).astype(np.float32)
+
+    def run(n_kv, n_rows):
+        fill = Nc + S - n_kv                               # synthetic keys/values so that S + Nc keys are attended
+        kv = np.tile(base, ((fill + 1023) // 1024, 1))[:fill]
         t0 = time.perf_counter()
-        st.layer(0, x, e0, pos, cache, rows=np.sort(order[n_rows:n_rows + extra]))
-        t_b = time.perf_counter() - t0
-        per_row = max(t_b - t_kv1, 1e-9) / extra          # the larger batch gives the better estimate
-        measured, rows_done = measured + t_b, rows_done + extra
-    t_layer = (t_kv1 - per_row) + per_row * S
-    t_stage = t_layer * cfg["n_layers"]
-    return {"value": S / t_stage, "unit": "tokens/s", "cores": int(os.environ.get("OMP_NUM_THREADS") or os.cpu_count()), "kind": "oracle",
-            "sample": f"fp64 oracle, layer 0 of {cfg['n_layers']}: K/V for all {S} tokens + {rows_done} sampled query rows "
-                      f"over {S + Nc} keys, {measured:.1f} s measured (+{t_init:.1f} s text side), "
-                      f"extrapolated to {S} rows x {cfg['n_layers']} layers = {t_stage:.0f} s per step"}
+        st.layer(0, x[:n_kv], e0, tuple(p[:n_kv] for p in pos), (kv, kv), rows=np.arange(n_rows))
+        return time.perf_counter() - t0
+
+    n_kv, n_rows = 8 * cores, 2 * cores                    # calibration: a few rows per thread
+    t_cal = run(n_kv, n_rows)
+    rate = (n_kv * f_kv + n_rows * f_row) / t_cal
+    n_kv = int(min(S, max(n_kv, 0.5 * budget_s * rate / f_kv)))
+    n_rows = int(min(n_kv, max(n_rows, 0.5 * budget_s * rate / f_row)))
+    t_big = run(n_kv, n_rows)
+    t_stage = t_big * S * (f_kv + f_row) / (n_kv * f_kv + n_rows * f_row) * cfg["n_layers"]
+    return {"value": S / t_stage, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"fp32 build of the oracle, layer 0 of {cfg['n_layers']}: K/V for {n_kv} of {S} tokens + {n_rows} sampled "
+                      f"query rows over {S + Nc} keys took {t_big:.1f} s ({t_cal:.1f} s calibration and {t_init:.1f} s text side "
+                      f"before it); scaled by algorithmic flops to {S} tokens x {cfg['n_layers']} layers = {t_stage:.0f} s per step"}
 
 
 def cache_ablation(args):
-    """Informational: the shape of the paper's feature-cache ablation (Table 3, with / without cache) on one
+    """Informational: the shape of the paper's feature-cache ablation (Table 4, with / without cache) on one
     stage.  Num_B = Num_C = 8 latent frames as in the paper's experiments: with the cache a pass feeds
     [B_{i-1} tail ; B_i] = 12 frames and attends to 4 cached frames; without it the pass feeds
     [B_{i-1} tail ; B_i ; B_{i+1} head] = 16 frames."""
@@ -278,7 +294,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="wan1p3b_stage")
+    ap.add_argument("--workload", default="wan14b_stage",
+                    help="wan14b_stage (default: the largest single-GPU stage configuration), wan1p3b_stage, or an "
+                         "informational one: wan1p3b_queue, wan1p3b_long, wan1p3b_latent, wan1p3b_ablation")
     ap.add_argument("--levels", type=int, default=8, help="noise levels T of the wan1p3b_long workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="print the per-class time table to stderr")
@@ -392,7 +410,7 @@ def main():
         achieved = fl / (dom_ms / dom_n * 1e-3) / 1e12
         roof = {"kernel": dominant, "bound": "mfma" if cfg["dtype"] == "bf16" else "alu", "achieved": achieved,
                 "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dominant)),
+                "traffic": measured_traffic(args.workload, dominant),
                 "avg_launch_ms": dom_ms / dom_n, "launches": dom_n}
     else:
         achieved = by / (dom_ms / dom_n * 1e-3) / 1e9
@@ -415,6 +433,8 @@ def main():
     if cfg["dtype"] == "bf16":
         # what the matrix cores sustain on this machine with nothing else running: zero vs pseudo-random operand bits
         res["mfma_issue_ceiling_tflops"] = {"zeros": B.probe_mfma_bf16("zeros"), "random": B.probe_mfma_bf16("random")}
+        # what a plain streaming pass of the LayerNorm's traffic shape and size (fp32 in, bf16 out) reaches
+        res["stream_copy_gbs_same_bytes_as_ln"] = B.probe_stream_f32_bf16(S * cfg["dim"])
     if not args.no_cpu_baseline and not queue:
         res["cpu_baseline"] = cpu_baseline(cfg, weights, text, blocks[1])
     print(json.dumps(res))

@@ -171,8 +171,8 @@ typedef struct {
  * for DP_ORDER_REVERSE), each pass lowers the block's level by one, and a block leaves after its
  * level-1 pass.  There are T * block_num passes.  *n_written receives the number of passes; if
  * capacity is smaller the call writes nothing and returns DP_ENOMEM (out may then be NULL).
- * Errors: DP_EINVAL (null cfg / n_written, non-positive sizes, frame indices or step numbers beyond
- * 2^31 - 1), DP_ENOMEM.
+ * Errors: DP_EINVAL (null cfg / n_written, non-positive sizes, num_c / 2 > num_b -- Sec. 3.2 takes the context
+ * from the adjacent block only --, frame indices or step numbers beyond 2^31 - 1), DP_ENOMEM.
  */
 int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry* out, int64_t capacity,
                           int64_t* n_written);
@@ -208,8 +208,8 @@ int dp_pipeline_simulate(int32_t n_devices, int32_t T, int32_t block_num, int32_
  *   random_words : host, at least (block_num - 1) * (num_b - 1) words (may be NULL if that is 0)
  *   pool_index   : host, out; *n_written receives the number of entries.  capacity too small: nothing
  *                  is written, DP_ENOMEM (pool_index may then be NULL)
- * Errors: DP_EINVAL (null cfg / n_written, block_num < 1, num_b < 1, num_c < 0, too few words, a pool beyond
- * 2^31 - 1 frames), DP_ENOMEM.
+ * Errors: DP_EINVAL (null cfg / n_written, block_num < 1, num_b < 1, num_c < 0, num_c / 2 > num_b, too few
+ * words, a pool beyond 2^31 - 1 frames), DP_ENOMEM.
  *
  * dp_noise_gather (device) materialises a block's initial noise: out[f, :] = pool[index[f], :].
  *   pool        : device, [pool_frames, frame_bytes] bytes, 16-byte aligned; frame_bytes % 16 == 0
@@ -315,6 +315,15 @@ int dp_stage_profile_end(dp_stage_t* stage, double* ms /* host [DP_PROF_COUNT] *
 enum { DP_PROBE_ZEROS = 0, DP_PROBE_RANDOM = 1 };
 int dp_probe_mfma_bf16(int32_t operand_mode, int32_t iters, float* scratch, int64_t scratch_floats,
                        void* hip_stream, double* tflops);
+
+/* Measurement aid: the rate (GB/s, read + written bytes) of a plain streaming pass with the traffic shape of the
+ * fused LayerNorm (4 bytes read and 2 bytes written per element): the library's fp32 -> bf16 conversion kernel
+ * run `iters` times over n elements, event-timed.  The bandwidth-bound kernels' achieved rates are reported next
+ * to this figure, measured in the same run on a buffer of the same size.
+ *   src : device float [n];  dst : device bfloat16 [n];  both 16-byte aligned, n a multiple of 8
+ * Synchronises the stream.  Errors: DP_EINVAL, DP_EHIP. */
+int dp_probe_stream_f32_bf16(const float* src, void* dst, int64_t n, int32_t iters, void* hip_stream,
+                             double* gbytes_per_s);
 
 /* Releases the host-side handle (device memory belongs to the caller).  NULL is allowed. */
 void dp_stage_free(dp_stage_t* stage);

@@ -22,6 +22,7 @@ def noise_assignment(block_num, num_b, num_c, words):
     Returns a list of block_num lists: block 1 has num_b + num_c // 2 entries, the others num_b.
     `words` is a sequence of at least (block_num - 1) * (num_b - 1) unsigned 32-bit integers."""
     half = num_c // 2
+    assert half <= num_b, "the excluded noises are those of a block's last Num_C/2 frames (Sec. 3.3); it has Num_B"
     pool = num_b + half
     blocks = [list(range(pool))]
     pos = 0

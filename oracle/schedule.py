@@ -27,6 +27,7 @@ def blockwise_schedule(T, block_num, num_b, num_c, first_block_frames=None, t_ma
     if first_block_frames is None:
         first_block_frames = num_b
     half = num_c // 2
+    assert half <= num_b, "the Num_C/2 context frames come from the adjacent block (Sec. 3.2), which has Num_B"
     frames = [first_block_frames] + [num_b] * (block_num - 1)
     starts = [0]
     for n in frames[:-1]:

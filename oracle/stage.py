@@ -77,11 +77,15 @@ class OracleStage:
         return e0.reshape(6, self.cfg["dim"])
 
     # -- one layer -----------------------------------------------------------
-    def layer(self, li, x, e0, pos, cache_kv, taps=None, rows=None):
+    def layer(self, li, x, e0, pos, cache_kv, taps=None, rows=None, block_kv=None):
         """x: [S, D] layer input for the whole block.  pos: (pf, py, px) of the block's tokens.
         cache_kv: (K_c, V_c) or None.  rows: optional index array; when given only those query rows
         are carried through (keys/values still come from every token) and the result is [len(rows), D].
-        Returns (x_out, K-hat, V)."""
+        block_kv: optional (K-hat, V) of tokens of the block that are NOT among the rows of x, computed
+        elsewhere (teacher forcing at sizes where keys/values for every token take minutes of CPU: x then
+        holds sampled tokens only, whose own keys/values are computed here and checked by the caller, and
+        the given rows are appended to the key/value list; softmax does not care about key order).
+        Returns (x_out, K-hat, V) with K-hat, V those computed here from x."""
         o, cfg, lw = self.ops, self.cfg, self.layers[li]
         h, d, eps = cfg["n_heads"], cfg["head_dim"], cfg["eps"]
         sh1, sc1, g1, sh2, sc2, g2 = (lw["mod"] + e0)
@@ -94,11 +98,13 @@ class OracleStage:
             x, hn = x[rows], hn[rows]
             pf, py, px = pf[rows], py[rows], px[rows]
         q = o.rope3d(o.rmsnorm(o.linear(hn, lw["wq"], lw["bq"]), lw["gq"], eps), h, d, pf, py, px, cfg["rope_theta"])
+        k_all, v_all = k, v
         if cache_kv is not None:
-            k_all = np.concatenate([cache_kv[0], k], axis=0)
-            v_all = np.concatenate([cache_kv[1], v], axis=0)
-        else:
-            k_all, v_all = k, v
+            k_all = np.concatenate([cache_kv[0], k_all], axis=0)
+            v_all = np.concatenate([cache_kv[1], v_all], axis=0)
+        if block_kv is not None:
+            k_all = np.concatenate([k_all, o.arr(block_kv[0])], axis=0)
+            v_all = np.concatenate([v_all, o.arr(block_kv[1])], axis=0)
         attn = o.attention(q, k_all, v_all, h)
         x1 = x + g1 * o.linear(attn, lw["wo"], lw["bo"])
         # cross-attention to the text tokens (current block only, no gate, no RoPE)

@@ -114,6 +114,8 @@ _lib.dp_pipeline_simulate.restype = C.c_int
 _lib.dp_pipeline_simulate.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
 _lib.dp_probe_mfma_bf16.restype = C.c_int
 _lib.dp_probe_mfma_bf16.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(C.c_double)]
+_lib.dp_probe_stream_f32_bf16.restype = C.c_int
+_lib.dp_probe_stream_f32_bf16.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.POINTER(C.c_double)]
 _lib.dp_stage_free.argtypes = [C.c_void_p]
 _lib.dp_last_error.restype = C.c_char_p
 _lib.dp_last_error.argtypes = []
@@ -372,6 +374,17 @@ def probe_mfma_bf16(operands="random", iters=20000, device="cuda"):
     stream = torch.cuda.current_stream().cuda_stream
     _check(_lib.dp_probe_mfma_bf16({"zeros": 0, "random": 1}[operands], iters, scratch.data_ptr(), scratch.numel(),
                                    stream, C.byref(out)), "dp_probe_mfma_bf16")
+    return out.value
+
+
+def probe_stream_f32_bf16(n, iters=20, device="cuda"):
+    """Rate (GB/s) of a plain fp32 -> bf16 streaming pass over n elements (the LayerNorm's traffic shape)."""
+    src = torch.ones(n, dtype=torch.float32, device=device)
+    dst = torch.empty(n, dtype=torch.bfloat16, device=device)
+    out = C.c_double()
+    stream = torch.cuda.current_stream().cuda_stream
+    _check(_lib.dp_probe_stream_f32_bf16(src.data_ptr(), dst.data_ptr(), n, iters, stream, C.byref(out)),
+           "dp_probe_stream_f32_bf16")
     return out.value
 
 

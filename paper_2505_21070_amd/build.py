@@ -35,10 +35,21 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def is_stale() -> bool:
+    """True when no library is there or a source or header is newer than it."""
+    if not os.path.exists(LIB):
+        return True
+    built = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)]
+    deps.append(os.path.join(os.path.dirname(HERE), "include", "dualparal.h"))
+    return any(os.path.getmtime(d) > built for d in deps if os.path.isfile(d))
+
+
 def ensure_built() -> str:
-    """For the scripts around the library (tests, bench, smoke): builds only if no library is there.  The
-    binding never calls this; without a library it raises."""
-    return LIB if os.path.exists(LIB) else build()
+    """For the scripts around the library (tests, bench, smoke): loads what is built, and builds only if no
+    library is there or a source is newer than it (so a stale binary is never tested).  The binding never
+    calls this; without a library it raises."""
+    return build() if is_stale() else LIB
 
 
 if __name__ == "__main__":

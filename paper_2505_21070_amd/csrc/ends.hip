@@ -46,8 +46,8 @@ __global__ void k_unpatchify(const float* __restrict__ in, float* __restrict__ l
   if (i < n) latent[patch_elem(i / P, (int)(i % P), tok, tw, C)] = in[i];
 }
 __global__ void k_euler(float* __restrict__ x, const float* __restrict__ v, int64_t n, float ds) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) x[i] = x[i] + ds * v[i];
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) x[i] = x[i] + ds * v[i];
 }
 
 static const char* validate(const dp_ends_config* c) {
@@ -190,7 +190,8 @@ extern "C" int dp_euler_step(float* x, const float* v, int64_t n, float sigma, f
   if (!x || !v) return dp_set_error(DP_EINVAL, "dp_euler_step: null pointer");
   if (!(sigma == sigma) || !(sigma_next == sigma_next)) return dp_set_error(DP_EINVAL, "dp_euler_step: sigma is NaN");
   (void)hipGetLastError();
-  k_euler<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)hip_stream>>>(x, v, n, sigma_next - sigma);
+  const int64_t blocks = (n + 255) / 256;                      // grid-stride beyond 2^20 blocks: any n fits
+  k_euler<<<(unsigned)(blocks < (1 << 20) ? blocks : (1 << 20)), 256, 0, (hipStream_t)hip_stream>>>(x, v, n, sigma_next - sigma);
   if (hipGetLastError() != hipSuccess) return dp_set_error(DP_EHIP, "dp_euler_step: the launch failed");
   return DP_OK;
 }

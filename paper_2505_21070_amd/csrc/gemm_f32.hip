@@ -11,7 +11,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, i
   __shared__ float Ws[16][64 + 4];   // [k][n]
   const int tid = threadIdx.x;
   const int tx = tid & 15, ty = tid >> 4;        // thread owns rows ty*4.., cols tx*4..
-  const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
+  const int64_t m0 = (int64_t)blockIdx.x * 64, n0 = (int64_t)blockIdx.y * 64;   // rows on x: no 65535-block limit
   float acc[4][4] = {};
   for (int64_t k0 = 0; k0 < K; k0 += 16) {
     // A tile: 64 rows x 16 k ; thread loads 4 elements
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, i
 void launch_gemm_f32(const float* A, int64_t lda, const float* W, int64_t ldw, int64_t M, int64_t N,
                      int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
   if (M <= 0 || N <= 0) return;
-  dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 63) / 64));
+  dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));     // N <= 6 * 8192, so grid.y stays small
   if (epi == EPI_STORE) k_gemm_f32<EPI_STORE><<<grid, 256, 0, st>>>(A, lda, W, ldw, M, N, K, e);
   else if (epi == EPI_GELU) k_gemm_f32<EPI_GELU><<<grid, 256, 0, st>>>(A, lda, W, ldw, M, N, K, e);
   else k_gemm_f32<EPI_RESID><<<grid, 256, 0, st>>>(A, lda, W, ldw, M, N, K, e);

@@ -6,7 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include "../../include/dualparal.h"
-#include "common.h"
+#include "kernels.h"
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -78,5 +78,30 @@ extern "C" int dp_probe_mfma_bf16(int32_t operand_mode, int32_t iters, float* sc
   }
   // blocks x 4 wavefronts x 4 accumulators x iters MFMAs of 2*32*32*16 flops
   *tflops = (double)kBlocks * 4 * 4 * (double)iters * 32768.0 / ((double)ms * 1e9);
+  return DP_OK;
+}
+
+// A plain streaming pass of the LayerNorm's traffic shape (4 bytes read, 2 bytes written per element, nothing
+// else): the library's own fp32 -> bf16 conversion kernel, event-timed.  What it reaches on a buffer of the same
+// size is the ceiling any kernel that must read the fp32 residual stream and write bf16 can be held against.
+extern "C" int dp_probe_stream_f32_bf16(const float* src, void* dst, int64_t n, int32_t iters, void* hip_stream,
+                                        double* gbytes_per_s) {
+  if (!src || !dst || !gbytes_per_s || n < 8 || n % 8 || iters < 1 || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15))
+    return dp_set_error(DP_EINVAL, "dp_probe_stream_f32_bf16: bad argument");
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return dp_set_error(DP_EHIP, "dp_probe_stream_f32_bf16: hipEventCreate failed");
+  launch_from_f32<bf16_t>(src, (bf16_t*)dst, n, st);                                   // warm-up
+  (void)hipEventRecord(e0, st);
+  for (int i = 0; i < iters; ++i) launch_from_f32<bf16_t>(src, (bf16_t*)dst, n, st);
+  (void)hipEventRecord(e1, st);
+  const hipError_t err = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (err == hipSuccess) (void)hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (err != hipSuccess || !(ms > 0.f)) return dp_set_error(DP_EHIP, "dp_probe_stream_f32_bf16: the timed launches failed");
+  *gbytes_per_s = (double)n * 6.0 * iters / ((double)ms * 1e6);
   return DP_OK;
 }

@@ -17,6 +17,9 @@ extern "C" int dp_blockwise_schedule(const dp_sched_config* cfg, dp_sched_entry*
   if (!cfg || !n_written) return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: null pointer");
   if (cfg->T < 1 || cfg->block_num < 1 || cfg->num_b < 1 || cfg->num_c < 0 || cfg->first_block_frames < 0)
     return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: non-positive size");
+  // Sec. 3.2 takes a block's num_c/2 context frames from the ADJACENT block; more than a block holds is undefined
+  if (cfg->num_c / 2 > cfg->num_b)
+    return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: num_c / 2 exceeds num_b (the context would reach beyond the neighbouring block)");
   if (cfg->order != DP_ORDER_REVERSE && cfg->order != DP_ORDER_SEQUENTIAL)
     return dp_set_error(DP_EINVAL, "dp_blockwise_schedule: unknown order");
   if (cfg->input != DP_INPUT_BLOCK && cfg->input != DP_INPUT_EXTENDED && cfg->input != DP_INPUT_NOCACHE)
@@ -124,6 +127,9 @@ extern "C" int dp_noise_assign(const dp_noise_config* cfg, const uint32_t* rando
     return dp_set_error(DP_EINVAL, "dp_noise_assign: bad block_num / num_b / num_c");
   if ((int64_t)cfg->num_b + cfg->num_c / 2 > INT32_MAX)
     return dp_set_error(DP_EINVAL, "dp_noise_assign: pool beyond 2^31 - 1 frames");
+  // Sec. 3.3 excludes the noises of the previous block's last num_c/2 frames; a block has only num_b
+  if (cfg->num_c / 2 > cfg->num_b)
+    return dp_set_error(DP_EINVAL, "dp_noise_assign: num_c / 2 exceeds num_b (a block has no num_c / 2 last frames)");
   const int32_t nb = cfg->num_b, half = cfg->num_c / 2, pool = nb + half;
   const int64_t need_words = (int64_t)(cfg->block_num - 1) * (nb - 1);
   if (n_words < need_words || (need_words > 0 && !random_words))

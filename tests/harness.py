@@ -7,7 +7,13 @@ from oracle.stage import OracleStage
 from paper_2505_21070_amd import synth
 
 FP32_TOL = 1e-4      # |gpu - ref| <= 1e-4 * max(1, |ref|), every element
-BF16_REL_L2 = 2e-2   # ||gpu - ref||_2 / ||ref||_2
+BF16_REL_L2 = 2e-2   # ||gpu - ref||_2 / ||ref||_2 over the whole tensor
+# bf16, per row: ||gpu_r - ref_r||_2 <= BF16_ROW_REL_L2 * max(||ref_r||_2, typical row norm of ref).  The global
+# bound alone lets a completely wrong row of a large tensor pass (one row of 6240 weighs 1.3 %); this one does
+# not: a wrong row has a relative error of order 1.  Measured worst rows are listed next to the derivation of
+# the tolerances in the design notes.
+BF16_ROW_REL_L2 = 5e-2
+MIN_ROW = 64         # rows shorter than this are folded together before the per-row bound is taken
 
 
 def gpu_stage(cfg, weights, text, **kw):
@@ -31,6 +37,27 @@ def to_np(t):
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
+def row_errors(got, ref):
+    """Per-row relative L2 error of a 2-D comparison, each row measured against max(its own norm, the typical
+    row norm), so that rows which are nearly zero in the reference do not blow the ratio up.  Rows shorter
+    than MIN_ROW elements are folded together first.  Returns (worst ratio, index of that row)."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    if got.ndim != 2 or got.size == 0:
+        got, ref = got.reshape(1, -1), ref.reshape(1, -1)
+    rows, cols = got.shape
+    if cols < MIN_ROW:
+        k = 1
+        while cols * k < MIN_ROW and rows % (2 * k) == 0:
+            k *= 2
+        got, ref = got.reshape(rows // k, cols * k), ref.reshape(rows // k, cols * k)
+    err = np.linalg.norm(got - ref, axis=1)
+    nrm = np.linalg.norm(ref, axis=1)
+    typical = np.linalg.norm(ref) / np.sqrt(ref.shape[0])
+    ratio = err / np.maximum(np.maximum(nrm, typical), 1e-30)
+    i = int(np.argmax(ratio)) if ratio.size else 0
+    return (float(ratio[i]) if ratio.size else 0.0), i
+
+
 def check(name, got, ref, dtype, report=None):
     """Asserts the build's tolerance; returns the error figures."""
     got = np.asarray(got, np.float64)
@@ -41,11 +68,14 @@ def check(name, got, ref, dtype, report=None):
     max_abs = float(err.max()) if err.size else 0.0
     max_rel = float((err / np.maximum(np.abs(ref), 1e-30)).max()) if err.size else 0.0
     rel_l2 = float(np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30))
+    worst_row, worst_at = row_errors(got, ref)
     if report is not None:
-        report[name] = dict(max_abs=max_abs, max_rel=max_rel, rel_l2=rel_l2)
+        report[name] = dict(max_abs=max_abs, max_rel=max_rel, rel_l2=rel_l2, worst_row=worst_row, worst_row_at=worst_at)
     if dtype == "f32":
         bad = err > FP32_TOL * np.maximum(1.0, np.abs(ref))
         assert not bad.any(), f"{name}: {int(bad.sum())} elements beyond 1e-4 (max_abs {max_abs:.3e}, max_rel {max_rel:.3e})"
     else:
         assert rel_l2 <= BF16_REL_L2, f"{name}: relative L2 {rel_l2:.3e} > 2e-2 (max_abs {max_abs:.3e})"
+        assert worst_row <= BF16_ROW_REL_L2, (f"{name}: row {worst_at} has relative L2 {worst_row:.3e} > "
+                                              f"{BF16_ROW_REL_L2} (whole tensor {rel_l2:.3e}, max_abs {max_abs:.3e})")
     return max_abs, max_rel, rel_l2

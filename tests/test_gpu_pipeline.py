@@ -1,11 +1,16 @@
 """Two pipeline stages on one GPU, each on its own HIP stream, running the block queue (Sec. 3.1): the hand-over
 x_out(stage 1) -> x_in(stage 2) is ordered by events only, so stage 1 may already work on the next block pass
 while stage 2 still runs the previous one.  Checks that the overlapped pipeline gives exactly what one handle
-holding all layers gives when it runs the same passes one after the other."""
+holding all layers gives when it runs the same passes one after the other, and that every pass equals the
+oracle's device pipeline: two oracle stages of one layer each, chained through eps^1 = E_theta_1(eps^0),
+eps^2 = E_theta_2(eps^1) (Eq. 1), each with its own feature cache."""
+import numpy as np
 import pytest
 import torch
 
-from harness import gpu_stage, to_dev
+from harness import check, gpu_stage, to_dev, to_np
+from oracle.noise import gather_frames, noise_assignment
+from oracle.stage import OracleStage
 from paper_2505_21070_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -19,8 +24,11 @@ def test_two_stage_pipeline_on_two_streams(name):
     nb, T, num_b, num_c = 4, 3, cfg["block_frames"], 2 * cfg["cache_frames"]
     pool_frames = num_b + num_c // 2
     gen = torch.Generator().manual_seed(12)
-    pool = to_dev(synth.noise_pool(cfg, pool_frames, gen), cfg)
-    idx = B.noise_assign(nb, num_b, num_c, synth.shuffle_words((nb - 1) * (num_b - 1), 13))
+    pool_host = synth.noise_pool(cfg, pool_frames, gen)
+    pool = to_dev(pool_host, cfg)
+    words = synth.shuffle_words((nb - 1) * (num_b - 1), 13)
+    idx = B.noise_assign(nb, num_b, num_c, words)
+    assert idx == noise_assignment(nb, num_b, num_c, words)
     xs = [B.noise_gather(pool, torch.tensor(i, dtype=torch.int32, device="cuda")).reshape(-1, cfg["dim"]) for i in idx]
     sched = B.blockwise_schedule(T, nb, num_b, num_c, pool_frames, 1000.0, "reverse")
     kw = dict(max_block_frames=pool_frames, max_abs_frames=pool_frames + nb * num_b)
@@ -66,6 +74,19 @@ def test_two_stage_pipeline_on_two_streams(name):
         else:   # the hand-over rounds the fp32 residual stream to bf16 once more than the single handle does
             d = (outs[p].float() - ref[p].float()).norm() / ref[p].float().norm()
             assert d < 2e-2, f"pass {p}: {d}"
+    # the oracle's two-device pipeline (Eq. 1, Sec. 3.1): stage j holds layer j and its own feature cache
+    wn = synth.to_numpy(w)
+    o_stages = [OracleStage(dict(cfg, n_layers=1), {"stage": wn["stage"], "layers": [wn["layers"][j]]}, text.numpy())
+                for j in range(2)]
+    xs_ref = [gather_frames(pool_host.numpy(), i).reshape(-1, cfg["dim"]) for i in idx]
+    for p, e in enumerate(sched):
+        x = xs_ref[e["block"] - 1]
+        for o in o_stages:
+            if e["cache_block"] == 0:
+                o.cache_update(0, 0)
+            x = o.forward(x, e["n_frames"], e["frame0"], e["timestep"])
+            o.cache_update(0, num_c // 2)
+        check(f"pipeline/pass{p}/step{e['step']}/block{e['block']}", to_np(outs[p]), x, cfg["dtype"])
     # the same pipeline run twice gives the same bits (no race between the two streams)
     outs2 = [torch.empty_like(o) for o in outs]
     for st in stages:

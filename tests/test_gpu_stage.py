@@ -52,6 +52,11 @@ def run_pair(name, seed, strong_gate, cache_mode, report=None):
     check(f"{name}/x_self", to_np(g.peek("x_self", li)), last["x_self"], dt, report)
     check(f"{name}/x_cross", to_np(g.peek("x_cross", li)), last["x_cross"], dt, report)
     check(f"{name}/ffn_branch", xres - to_np(g.peek("x_cross", li)), r - last["x_cross"], dt, report)
+    # adaLN modulation rows of every layer (shift1, scale1, gate1, shift2, scale2, gate2) at the last timestep:
+    # fp32 arithmetic on both storage types, so the fp32 tolerance applies to both
+    e0 = o.modulation(T_CUR)
+    for l in range(cfg["n_layers"]):
+        check(f"{name}/mod{l}", to_np(g.peek("mod", l)), o.layers[l]["mod"] + e0, "f32", report)
     return g, o, (cfg, w, text, blocks), (y, r)
 
 

@@ -54,6 +54,11 @@ def test_schedule_capacity_and_bad_input(B):
     bad = B.SchedConfig(4, 3, 4, 4, 0, 0, 1000.0, 3)                       # unknown input variant
     assert B._lib.dp_blockwise_schedule(C.byref(bad), arr, 5, C.byref(n)) == B.DP_EINVAL
     assert B._lib.dp_blockwise_schedule(None, arr, 5, C.byref(n)) == B.DP_EINVAL
+    bad = B.SchedConfig(4, 3, 2, 6, 0, 0, 1000.0)                          # num_c / 2 > num_b: outside Sec. 3.2
+    assert B._lib.dp_blockwise_schedule(C.byref(bad), arr, 5, C.byref(n)) == B.DP_EINVAL
+    assert "num_c" in B.last_error()
+    with pytest.raises(AssertionError):
+        oracle_schedule(4, 3, 2, 6)
 
 
 def test_bubble_ratio_matches_oracle_and_paper(B):
@@ -102,6 +107,12 @@ def test_noise_assignment_bad_input(B):
     bad = B.NoiseConfig(0, 4, 4)
     assert B._lib.dp_noise_assign(C.byref(bad), words, 6, None, 0, C.byref(n)) == B.DP_EINVAL
     assert b"dp_noise_assign" in B._lib.dp_last_error()
+    bad = B.NoiseConfig(3, 2, 6)                                           # num_c / 2 > num_b: outside Sec. 3.3
+    assert B._lib.dp_noise_assign(C.byref(bad), words, 6, None, 0, C.byref(n)) == B.DP_EINVAL
+    assert b"num_c" in B._lib.dp_last_error()
+    from oracle.noise import noise_assignment
+    with pytest.raises(AssertionError):
+        noise_assignment(3, 2, 6, list(range(6)))
 
 
 def test_pipeline_simulation_matches_oracle(B):

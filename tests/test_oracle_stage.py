@@ -114,6 +114,32 @@ def test_sampled_rows_match_full_layer(oracle_built):
     np.testing.assert_array_equal(k, k2)
 
 
+def test_teacher_forced_block_keys_match_full_layer(oracle_built):
+    """The layer fed only sampled tokens, with the other tokens' keys/values handed in (here: those of the full
+    run), gives the full layer's rows: the hook used at sizes where keys/values for every token take minutes."""
+    cfg, w, text, blocks, st = make("small_bf16")
+    nf, nc = cfg["block_frames"], cfg["cache_frames"]
+    tok = cfg["tok_h"] * cfg["tok_w"]
+    st.forward(blocks[0].numpy(), nf, nf, 625.0)
+    st.cache_update(0, nc)
+    cache = st.cache[0]
+    x = blocks[1].numpy().astype(np.float64)
+    e0 = st.modulation(500.0)
+    pos = token_positions(nf, 0, cfg["tok_h"], cfg["tok_w"])
+    full, k, v = st.layer(0, x, e0, pos, cache)
+    sample = np.array([0, 3, 71, 72, 100, nf * tok - 1])
+    others = np.setdiff1d(np.arange(nf * tok), sample)
+    q_rows = np.array([1, 4, 5])                       # positions inside `sample`
+    part, k_s, v_s = st.layer(0, x[sample], e0, tuple(p[sample] for p in pos), cache, rows=q_rows,
+                              block_kv=(k[others], v[others]))
+    np.testing.assert_allclose(part, full[sample[q_rows]], rtol=0, atol=1e-12)
+    np.testing.assert_array_equal(k_s, k[sample])
+    np.testing.assert_array_equal(v_s, v[sample])
+    # leaving the other tokens' keys out changes the rows (the hook is not vacuous)
+    alone, _, _ = st.layer(0, x[sample], e0, tuple(p[sample] for p in pos), cache, rows=q_rows)
+    assert np.abs(alone - part).max() > 1e-4
+
+
 def test_cache_memory_bound(oracle_built):
     """Live cache per layer is Num_C/2 frames of K and V (appendix efficiency analysis)."""
     cfg, w, text, blocks, st = make("tiny")
