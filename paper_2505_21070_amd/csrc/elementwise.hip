@@ -77,53 +77,83 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t st) {   // bytes % 4 ==
 }
 
 // ---------------------------------------------------------------- LayerNorm + modulate
-// One wavefront per row; the row lives in registers (NCH float4 per lane), so x is read once.
-// Two-pass statistics (mean, then centred variance) in fp32.
+// NW wavefronts per row (1: a wavefront owns a row, 4 rows per block; 4: the block owns one row and the
+// statistics meet in LDS); the row lives in registers (NCH float4 per lane), so x is read once.  Two-pass
+// statistics (mean, then centred variance) in fp32, partial sums added in a fixed order.
+// The row is read and the result written with non-temporal accesses: both are streamed once, and on this part
+// a kernel that reads 4 and writes 2 bytes per element runs 1.4-1.7x faster that way (measured on flushed
+// caches: 5120-wide rows 152 -> 89 us for 442 MB, 1536-wide rows 24 -> 15 us for 57 MB), faster than a plain
+// conversion pass of the same bytes.  Wide rows gain another 25 % from four wavefronts per row (more rows in
+// flight per compute unit, 5 instead of 20 outstanding loads per lane).
 // xin != null: the row is read from xin (bf16) instead of x, and x receives its fp32 copy (the first
 // LayerNorm of a stage, which thereby also fills the fp32 residual stream).
-template <typename T, int NCH>
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+template <typename T, int NCH, int NW>
 __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, const bf16_t* __restrict__ xin,
                                                      T* __restrict__ out, int64_t S, int D, float eps,
                                                      const float* __restrict__ mul,
                                                      const float* __restrict__ add, float plus) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= S) return;
-  float4* xr = (float4*)(x + row * D);
+  static_assert(NW == 1 || NW == 2 || NW == 4, "wavefronts per row");
+  constexpr int RPB = 4 / NW;                        // rows per block
+  __shared__ float red[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int64_t row = (int64_t)blockIdx.x * RPB + w / NW;
+  const int part = (w % NW) * 64 + lane;             // this lane's float4 slot inside a run of NW * 64 slots
+  const bool live = row < S;                         // rows of a block end together only when NW > 1 shares them
   const int nvec = D >> 2;
-  float4 v[NCH];
+  f32x4_t v[NCH];
   float sum = 0.f;
+  if (live) {
+    f32x4_t* xr = (f32x4_t*)(x + row * D);
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    const int idx = i * 64 + lane;
-    if (idx < nvec) {
-      if (xin) {
-        const uint2 w = ((const uint2*)(xin + row * D))[idx];
-        v[i] = make_float4(bf16_to_f32((bf16_t)(w.x & 0xffff)), bf16_to_f32((bf16_t)(w.x >> 16)),
-                           bf16_to_f32((bf16_t)(w.y & 0xffff)), bf16_to_f32((bf16_t)(w.y >> 16)));
-        xr[idx] = v[i];
-      } else {
-        v[i] = xr[idx];
+    for (int i = 0; i < NCH; ++i) {
+      const int idx = i * (NW * 64) + part;
+      if (idx < nvec) {
+        if (xin) {
+          const u32x2_t wv = __builtin_nontemporal_load((const u32x2_t*)(xin + row * D) + idx);
+          v[i] = f32x4_t{bf16_to_f32((bf16_t)(wv.x & 0xffff)), bf16_to_f32((bf16_t)(wv.x >> 16)),
+                         bf16_to_f32((bf16_t)(wv.y & 0xffff)), bf16_to_f32((bf16_t)(wv.y >> 16))};
+          xr[idx] = v[i];
+        } else {
+          v[i] = __builtin_nontemporal_load(xr + idx);
+        }
+        sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
       }
-      sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+      else v[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
-    else v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  } else {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) v[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
-  const float mean = wave_sum(sum) / (float)D;
+  // sum over the row's NW wavefronts (consecutive wavefronts of the block), in wavefront order
+  auto row_sum = [&](float part_sum, int slot) __attribute__((always_inline)) {
+    float t = wave_sum(part_sum);
+    if constexpr (NW > 1) {
+      if (lane == 0) red[slot][w] = t;
+      __syncthreads();
+      t = 0.f;
+#pragma unroll
+      for (int i = 0; i < NW; ++i) t += red[slot][(w / NW) * NW + i];
+    }
+    return t;
+  };
+  const float mean = row_sum(sum, 0) / (float)D;
   float sq = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
-    const int idx = i * 64 + lane;
+    const int idx = i * (NW * 64) + part;
     if (idx < nvec) {
       const float a = v[i].x - mean, b = v[i].y - mean, c = v[i].z - mean, d = v[i].w - mean;
       sq += (a * a + b * b) + (c * c + d * d);
     }
   }
-  const float rstd = rsqrtf(wave_sum(sq) / (float)D + eps);
+  const float rstd = rsqrtf(row_sum(sq, 1) / (float)D + eps);
+  if (!live) return;
   T* orow = out + row * D;
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
-    const int idx = i * 64 + lane;
+    const int idx = i * (NW * 64) + part;
     if (idx < nvec) {
       const float4 m = ((const float4*)mul)[idx];
       const float4 a = ((const float4*)add)[idx];
@@ -132,10 +162,10 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
       const float r2 = (v[i].z - mean) * rstd * (m.z + plus) + a.z;
       const float r3 = (v[i].w - mean) * rstd * (m.w + plus) + a.w;
       if constexpr (sizeof(T) == 2) {
-        uint2 pk; pk.x = pack_bf16x2(r0, r1); pk.y = pack_bf16x2(r2, r3);
-        ((uint2*)orow)[idx] = pk;
+        u32x2_t pk; pk.x = pack_bf16x2(r0, r1); pk.y = pack_bf16x2(r2, r3);
+        __builtin_nontemporal_store(pk, (u32x2_t*)orow + idx);
       } else {
-        ((float4*)orow)[idx] = make_float4(r0, r1, r2, r3);
+        __builtin_nontemporal_store(f32x4_t{r0, r1, r2, r3}, (f32x4_t*)orow + idx);
       }
     }
   }
@@ -143,12 +173,18 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
 template <typename T>
 void launch_ln_modulate(float* x, const bf16_t* xin, T* out, int64_t S, int D, float eps, const float* mul,
                         const float* add, int plus_one, hipStream_t st) {
-  const int grid = cdiv(S, 4);
+  if (S <= 0) return;
   const float plus = plus_one ? 1.f : 0.f;
-  if (D <= 256) k_ln_modulate<T, 1><<<grid, 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus);
-  else if (D <= 2048) k_ln_modulate<T, 8><<<grid, 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus);
-  else if (D <= 5120) k_ln_modulate<T, 20><<<grid, 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus);
-  else k_ln_modulate<T, 32><<<grid, 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus);   // D <= 8192
+#define LN_CASE(NCH, NW) k_ln_modulate<T, NCH, NW><<<cdiv(S, 4 / NW), 256, 0, st>>>(x, xin, out, S, D, eps, mul, add, plus)
+  if (D <= 256) LN_CASE(1, 1);
+  else if (D <= 1536) LN_CASE(6, 1);
+  else if (D <= 2048) LN_CASE(8, 1);
+  else if (D <= 3072) LN_CASE(3, 4);
+  else if (D <= 4096) LN_CASE(4, 4);
+  else if (D <= 5120) LN_CASE(5, 4);
+  else if (D <= 6144) LN_CASE(6, 4);
+  else LN_CASE(8, 4);                                  // D <= 8192
+#undef LN_CASE
 }
 template void launch_ln_modulate<float>(float*, const bf16_t*, float*, int64_t, int, float, const float*, const float*, int, hipStream_t);
 template void launch_ln_modulate<bf16_t>(float*, const bf16_t*, bf16_t*, int64_t, int, float, const float*, const float*, int, hipStream_t);
