@@ -269,6 +269,24 @@ int dp_ends_init(const dp_ends_config* cfg, const dp_ends_weights* weights, void
 int dp_embed_forward(dp_ends_t* ends, const float* latent, void* x_out, int32_t n_frames, void* hip_stream);
 int dp_head_forward(dp_ends_t* ends, const void* x_in, float timestep, float* v_out, int32_t n_frames,
                     void* hip_stream);
+/* dp_head_forward for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid allocation.  No handle and no workspace: what dp_head_forward keeps in the caller's
+ * workspace lives in a 64 MiB device array inside the library (one copy per GPU, held until the process ends),
+ * and the call itself allocates nothing, on the device or the host, and issues kernel launches only.
+ *   cfg, weights : host structs as for dp_ends_init (w_pe / b_pe are not looked at); cfg->max_frames only bounds
+ *                  n_frames
+ *   x_in         : device [n_frames*tok_h*tok_w, dim] tokens in cfg->dtype;  v_out : device float32
+ *                  [n_frames, 2*tok_h, 2*tok_w, channels], as for dp_head_forward, whose result it reproduces bit
+ *                  for bit
+ * Size limit: roundup(n_frames*tok_h*tok_w, 256) * (dim * (4 + element size) + 16 * channels) plus a few vectors
+ * must fit the 64 MiB (e.g. 4 frames of 30 x 52 tokens at dim 1536 in bf16); beyond it nothing is launched and
+ * the call returns DP_ENOMEM.  The output head works token by token, so larger inputs can be fed frame by frame.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race; calls ordered on one stream do not.  Asynchronous on hip_stream.
+ * Errors: DP_EINVAL (null pointer, invalid cfg, n_frames outside [1, max_frames], NaN timestep), DP_ENOMEM (see
+ * above), DP_EHIP. */
+int dp_head_forward_static(const dp_ends_config* cfg, const dp_ends_weights* weights, const void* x_in,
+                           float timestep, float* v_out, int32_t n_frames, void* hip_stream);
 /* x[i] += (sigma_next - sigma) * v[i] for n float32 elements; x and v must not overlap. */
 int dp_euler_step(float* x, const float* v, int64_t n, float sigma, float sigma_next, void* hip_stream);
 void dp_ends_free(dp_ends_t* ends);

@@ -106,6 +106,9 @@ _lib.dp_embed_forward.restype = C.c_int
 _lib.dp_embed_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
 _lib.dp_head_forward.restype = C.c_int
 _lib.dp_head_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_int32, C.c_void_p]
+_lib.dp_head_forward_static.restype = C.c_int
+_lib.dp_head_forward_static.argtypes = [C.POINTER(EndsConfig), C.POINTER(EndsWeights), C.c_void_p, C.c_float, C.c_void_p,
+                                        C.c_int32, C.c_void_p]
 _lib.dp_euler_step.restype = C.c_int
 _lib.dp_euler_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_float, C.c_void_p]
 _lib.dp_ends_free.restype = None
@@ -322,6 +325,26 @@ class Ends:
             self.close()
         except Exception:
             pass
+
+
+def head_forward_static(cfg, weights, channels, x, timestep, n_frames, out, stream=None):
+    """dp_head_forward_static: the output head without handle or workspace.  `out` is the caller's float32
+    [n_frames, 2*tok_h, 2*tok_w, channels] device tensor (the call itself allocates nothing)."""
+    dt = DP_BF16 if cfg["dtype"] == "bf16" else DP_F32
+    td = torch.bfloat16 if dt == DP_BF16 else torch.float32
+    conf = EndsConfig(cfg["dim"], cfg["tok_h"], cfg["tok_w"], channels, n_frames, dt, cfg["freq_dim"], cfg["eps"])
+    ew = EndsWeights()
+    for n in ENDS_FIELDS:
+        t = weights[n]
+        assert t.is_cuda and t.dtype == td and t.is_contiguous(), n
+        setattr(ew, n, t.data_ptr())
+    tok = cfg["tok_h"] * cfg["tok_w"]
+    assert x.is_cuda and x.dtype == td and x.is_contiguous() and tuple(x.shape) == (n_frames * tok, cfg["dim"])
+    assert out.is_cuda and out.dtype == torch.float32 and out.is_contiguous()
+    assert tuple(out.shape) == (n_frames, 2 * cfg["tok_h"], 2 * cfg["tok_w"], channels)
+    _check(_lib.dp_head_forward_static(C.byref(conf), C.byref(ew), x.data_ptr(), float(timestep), out.data_ptr(), n_frames,
+                                       _stream_handle(stream)), "dp_head_forward_static")
+    return out
 
 
 def euler_step(x, v, sigma, sigma_next, stream=None):

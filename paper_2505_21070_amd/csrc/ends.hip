@@ -9,6 +9,7 @@
 // Latents and velocities are fp32; tokens are in the stage's storage type.  The GEMMs, LayerNorm and timestep
 // MLP are the stage's kernels.
 #include <cstdint>
+#include <mutex>
 #include <new>
 
 #include "../../include/dualparal.h"
@@ -181,6 +182,90 @@ extern "C" int dp_head_forward(dp_ends_t* s, const void* x_in, float timestep, f
   if (s->cfg.dtype == DP_BF16) head_typed<bf16_t>(s, x_in, timestep, v_out, n_frames, st);
   else head_typed<float>(s, x_in, timestep, v_out, n_frames, st);
   if (hipGetLastError() != hipSuccess) return dp_set_error(DP_EHIP, "dp_head_forward: a launch failed");
+  return DP_OK;
+}
+
+// ------------------------------------------------------------------------------------------ no allocation
+// dp_head_forward for callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+// that forbid it): no handle and no workspace.  Everything dp_head_forward keeps in the caller's workspace (the
+// timestep-MLP vectors, the fp32 copy of the tokens, the normalised tokens, the fp32 result before the scatter,
+// the repacked head matrix) lives in one file-scope device array instead.  Each GPU the library runs on holds its
+// own copy of the array at its own address, looked up once per device; host code only ever uses that address.
+constexpr size_t kHeadScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kHeadScratchBytes];
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[64] = {};                 // by device ordinal; filled on a device's first call
+
+static int head_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+    return dp_set_error(DP_EHIP, "dp_head_forward_static: no current device (or an ordinal beyond 63)");
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p)
+      return dp_set_error(DP_EHIP, "dp_head_forward_static: hipGetSymbolAddress failed");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DP_OK;
+}
+
+// the head's share of carve(), sized for the frames of this call
+static size_t carve_head(dp_ends* s, void* base, int n_frames) {
+  const dp_ends_config& c = s->cfg;
+  const int64_t E = c.dtype == DP_BF16 ? 2 : 4, D = c.dim;
+  s->tok = (int64_t)c.tok_h * c.tok_w;
+  s->Smax = s->tok * n_frames;
+  s->Spad = rup(s->Smax, 256);
+  s->P = 4 * (int64_t)c.channels;
+  char* b = (char*)base; size_t off = 0;
+  auto take = [&](size_t bytes) { off = (size_t)rup((int64_t)off, 256); void* p = b ? b + off : nullptr; off += bytes; return p; };
+  s->patches = nullptr; s->w_pe_t = nullptr;
+  s->h = take(s->Spad * D * E);
+  s->x32 = (float*)take(s->Spad * D * 4);
+  s->out32 = (float*)take(s->Spad * s->P * 4);
+  s->w_head_t = take(rup(s->P, 256) * D * E);
+  s->tau = (float*)take(c.freq_dim * 4);
+  s->e1 = (float*)take(GEMV_MAX_SLICES * D * 4); s->e = (float*)take(GEMV_MAX_SLICES * D * 4);
+  s->mhead = (float*)take(2 * D * 4); s->mod = (float*)take(2 * D * 4);
+  return (size_t)rup((int64_t)off, 256);
+}
+
+extern "C" int dp_head_forward_static(const dp_ends_config* cfg, const dp_ends_weights* w, const void* x_in,
+                                      float timestep, float* v_out, int32_t n_frames, void* hip_stream) {
+  const char* why = validate(cfg);
+  if (why) return dp_set_error(DP_EINVAL, why);
+  if (!w || !x_in || !v_out) return dp_set_error(DP_EINVAL, "dp_head_forward_static: null pointer");
+  if (!w->m_head || !w->w_head || !w->b_head || !w->wt1 || !w->bt1 || !w->wt2 || !w->bt2)
+    return dp_set_error(DP_EINVAL, "dp_head_forward_static: null weight pointer");
+  if (n_frames < 1 || n_frames > cfg->max_frames) return dp_set_error(DP_EINVAL, "dp_head_forward_static: n_frames outside [1, max_frames]");
+  if (!(timestep == timestep)) return dp_set_error(DP_EINVAL, "dp_head_forward_static: timestep is NaN");
+  dp_ends s;                                            // host struct on the stack: nothing is allocated
+  s.cfg = *cfg; s.w = *w;
+  if (carve_head(&s, nullptr, n_frames) > kHeadScratchBytes)
+    return dp_set_error(DP_ENOMEM, "dp_head_forward_static: this many tokens need more than the 64 MiB of static scratch; "
+                                   "call it per frame or use dp_head_forward with a workspace");
+  void* base = nullptr;
+  const int rc = head_scratch(&base);
+  if (rc != DP_OK) return rc;
+  carve_head(&s, base, n_frames);
+  hipStream_t st = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  const int64_t D = cfg->dim, S = s.tok * n_frames;
+  const bool bf = cfg->dtype == DP_BF16;
+  // the array keeps the last call's contents: rows of the GEMM operand beyond this call's tokens are cleared with
+  // a fill kernel (no memset call, so the entry point can be captured), the rest is overwritten below
+  if (s.Spad > S) launch_fill_zero((char*)s.h + S * D * (bf ? 2 : 4), (size_t)((s.Spad - S) * D * (bf ? 2 : 4)), st);
+  if (bf) {
+    launch_transpose_pad<bf16_t>((const bf16_t*)w->w_head, D, s.P, (bf16_t*)s.w_head_t, rup(s.P, 256), st);
+    launch_to_f32<bf16_t>((const bf16_t*)w->m_head, s.mhead, 2 * D, st);
+    head_typed<bf16_t>(&s, x_in, timestep, v_out, n_frames, st);
+  } else {
+    launch_to_f32<float>((const float*)w->m_head, s.mhead, 2 * D, st);
+    head_typed<float>(&s, x_in, timestep, v_out, n_frames, st);
+  }
+  if (hipGetLastError() != hipSuccess) return dp_set_error(DP_EHIP, "dp_head_forward_static: a launch failed");
   return DP_OK;
 }
 
