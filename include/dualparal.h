@@ -122,13 +122,25 @@ int dp_stage_forward(dp_stage_t* stage, const void* x_in, void* x_out, int32_t n
  * values of frames [first_frame, first_frame + n_frames) of the block the last dp_stage_forward
  * processed (frame indices relative to that block).  The cached keys carry their absolute
  * positions, so the next block may lie before or after them.  n_frames == 0 empties the cache.
- * No data moves and nothing is launched: the frames stay where the forward wrote them, and the next
- * forward writes its own keys and values directly before or after them in the per-layer buffer (which
- * has room for two blocks plus the cache).  hip_stream is accepted for symmetry and not used.
+ * May be called again for other frames of the same block; the last call counts.
+ * In the paper's geometry (blocks of max_block_frames frames handing over their first or last
+ * max_cache_frames frames) no data moves and nothing is launched: the frames stay where the forward wrote
+ * them, and the next forward writes its own keys and values directly before or after them in the per-layer
+ * buffer of max_block_frames + 2 * max_cache_frames frame positions.  Only where a block of max_block_frames
+ * frames would fit on neither side of the retained range is the range copied, by kernels on hip_stream (the
+ * stream of the forward calls), into the buffer's free space: 2 * n_frames * tok_h * tok_w * dim elements read
+ * and written per layer.
  * Errors: DP_ESTATE (no forward yet), DP_EINVAL (range outside the last block or above
- * max_cache_frames).
+ * max_cache_frames), DP_EHIP.
  */
 int dp_cache_update(dp_stage_t* stage, int32_t first_frame, int32_t n_frames, void* hip_stream);
+
+/* Bytes of self-attention key/value storage a stage of this geometry keeps per layer (cached range + current
+ * block, keys and transposed values): 2 * (max_block_frames + 2 * max_cache_frames) frames of tok_h * tok_w * dim
+ * elements, plus at most 127 key positions of alignment padding.  With max_block_frames = Num_B and
+ * max_cache_frames = Num_C / 2 that is the (Num_B + Num_C) * KV of the paper's memory analysis (Table 1: KV =
+ * one frame's keys and values in one layer).  0 if the config is invalid. */
+size_t dp_stage_kv_bytes(const dp_stage_config* cfg);
 
 /* Queue schedule of block-wise denoising (Sec. 3.1, 3.2, 3.3). */
 enum { DP_ORDER_REVERSE = 0 /* tail to head, the paper's choice */, DP_ORDER_SEQUENTIAL = 1 /* head to tail */ };
@@ -312,7 +324,7 @@ int dp_stage_peek(dp_stage_t* stage, int32_t what, int32_t layer, float* dst, in
  * recorded events and writes, for each of the DP_PROF_COUNT classes, the summed milliseconds and the
  * number of launches into two host arrays, then stops collecting.  At most 16384 launches are recorded
  * per begin/end pair; later ones are not timed.  Events are host-side objects; no device memory is
- * allocated.  DP_PROF_CACHE_COPY never reports launches: the cache hand-over moves no data.
+ * allocated.  DP_PROF_CACHE_COPY reports launches only for the cache hand-overs that had to copy.
  * Errors: DP_EINVAL, DP_EHIP. */
 enum { DP_PROF_LN = 0, DP_PROF_QKV_GEMM = 1, DP_PROF_NORM_ROPE = 2, DP_PROF_SELF_ATTN = 3,
        DP_PROF_OPROJ_GEMM = 4, DP_PROF_CROSS_Q_GEMM = 5, DP_PROF_CROSS_ATTN = 6, DP_PROF_CROSS_O_GEMM = 7,

@@ -56,6 +56,8 @@ class SchedEntry(C.Structure):
 
 _lib.dp_stage_workspace_bytes.restype = C.c_size_t
 _lib.dp_stage_workspace_bytes.argtypes = [C.POINTER(StageConfig)]
+_lib.dp_stage_kv_bytes.restype = C.c_size_t
+_lib.dp_stage_kv_bytes.argtypes = [C.POINTER(StageConfig)]
 _lib.dp_stage_init.restype = C.c_int
 _lib.dp_stage_init.argtypes = [C.POINTER(StageConfig), C.POINTER(StageWeights), C.c_void_p, C.c_void_p, C.c_size_t,
                                C.c_void_p, C.POINTER(C.c_void_p)]
@@ -156,6 +158,10 @@ def make_config(cfg, max_block_frames=None, max_cache_frames=None, max_abs_frame
 
 def workspace_bytes(config):
     return int(_lib.dp_stage_workspace_bytes(C.byref(config)))
+
+
+def kv_bytes_per_layer(config):
+    return int(_lib.dp_stage_kv_bytes(C.byref(config)))
 
 
 def _stream_handle(stream):

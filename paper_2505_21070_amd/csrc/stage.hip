@@ -71,7 +71,7 @@ struct dp_stage {
   dp_stage_weights w;
   std::vector<dp_layer_weights> lw;
   std::vector<LayerMem> lm;
-  int64_t tok, Smax, Ncmax, Spad, Lpad, Ltpad, esz;
+  int64_t tok, Smax, Ncmax, Spad, Lfit, Lpad, Ltpad, esz;
   // shared activations
   float* xres; void* hbuf; void* raw; void* qbuf; void* attn_o; void* mid;
   void* textpad; void* ctx; void* ctx_mid; void* wtmp;
@@ -84,9 +84,10 @@ struct dp_stage {
   float *qssq, *kssq; float2* rope_tok; int ssq_np, cross_np = 0; bool heads_epi; bool launch_ok = true;
   // state
   // Key buffer geometry (rows of kbuf = columns of vtbuf, the same in every layer).  The last block's keys
-  // sit at [blk0, blk0 + last_S); the feature cache is the sub-range [cache0, cache0 + cache_len) of it that
-  // dp_cache_update named.  The next block is written directly before or directly after the cache, so the
-  // keys an attention call reads are always one contiguous range and retaining frames moves no data.
+  // sit at [blk0, blk0 + last_S); the feature cache is the range [cache0, cache0 + cache_len): the sub-range
+  // of the last block that dp_cache_update named, left where it is whenever a maximal block still fits on one
+  // side of it, else a copy of it in the free space beside the last block.  The next block is written directly
+  // before or directly after the cache, so the keys an attention call reads are always one contiguous range.
   int64_t blk0 = 0, cache0 = 0, cache_len = 0, last_S = 0; int last_frames = 0;
 };
 
@@ -142,7 +143,11 @@ static size_t carve(dp_stage* s, void* base) {
   s->Smax = s->tok * c.max_block_frames;
   s->Ncmax = s->tok * c.max_cache_frames;
   s->Spad = rup(s->Smax, 256);
-  s->Lpad = rup(2 * s->Smax + s->Ncmax, 64) + 64;     // a block fits on one side of any cached range
+  // Key positions per layer: Num_B + Num_C frames when the block limit is Num_B and the cache limit Num_C / 2,
+  // the live K/V of the paper's memory analysis (Table 1).  dp_cache_update keeps the retained range where a
+  // maximal block fits on one side of it (see there); + one 64-key tile of padding for the attention loads.
+  s->Lfit = s->Smax + 2 * s->Ncmax;
+  s->Lpad = rup(s->Lfit, 64) + 64;
   s->Ltpad = rup(c.text_len, 256);
   const int64_t D = c.dim, F = c.ffn_dim, E = s->esz, L = c.n_layers;
   Carver cv(base);
@@ -380,7 +385,7 @@ static void forward_typed(dp_stage* s, const void* x_in, void* x_out, int n_fram
        launch_mod_add<T>(s->mtab, s->e0, gemv_slices((int)D, (int)(6 * D)), (const T*)s->w.bm, s->mod, c.n_layers, (int)(6 * D), st));
   const int64_t kv_hs = s->Lpad * d;        // head stride of kbuf
   // where this block's keys go: directly before the cached range if it fits there, else directly after it
-  // (the buffer holds 2 * Smax + Ncmax positions, so one side always has room)
+  // (dp_cache_update left the cache where one side has room for a maximal block)
   int64_t blk0 = 0, key0 = 0;
   if (s->cache_len > 0) {
     if (s->cache0 >= S) { blk0 = s->cache0 - S; key0 = blk0; }
@@ -470,6 +475,8 @@ extern "C" int dp_stage_forward(dp_stage_t* s, const void* x_in, void* x_out, in
   if (frame0 < 0 || (int64_t)frame0 + n_frames > s->cfg.max_abs_frames)
     return fail(DP_EINVAL, "dp_stage_forward: frames [%d, %lld) outside [0, %d)", frame0, (long long)frame0 + n_frames, s->cfg.max_abs_frames);
   if (!(timestep == timestep)) return fail(DP_EINVAL, "dp_stage_forward: timestep is NaN");
+  if (s->cache_len > 0 && s->cache0 < s->tok * n_frames && s->cache0 + s->cache_len + s->tok * n_frames > s->Lfit)
+    return fail(DP_ESTATE, "dp_stage_forward: no room for the block beside the cached range");   // dp_cache_update rules this out
   hipStream_t st = (hipStream_t)hip_stream;
   (void)hipGetLastError();
   s->launch_ok = true;
@@ -483,6 +490,17 @@ extern "C" int dp_stage_forward(dp_stage_t* s, const void* x_in, void* x_out, in
 }
 
 // ------------------------------------------------------------------------------------------ cache
+// rows [src, src + n) of every layer's key buffer and columns [src, src + n) of its transposed value buffer
+// to [dst, dst + n); the ranges must not overlap
+template <typename T>
+static void move_cache(dp_stage* s, int64_t src, int64_t dst, int64_t n, hipStream_t st) {
+  const int h = s->cfg.n_heads, d = s->cfg.head_dim;
+  for (LayerMem& m : s->lm) {
+    launch_copy2d<T>((const T*)m.kbuf + src * d, s->Lpad * d, (T*)m.kbuf + dst * d, s->Lpad * d, h, n * d, st);
+    launch_copy2d<T>((const T*)m.vtbuf + src, s->Lpad, (T*)m.vtbuf + dst, s->Lpad, (int64_t)h * d, n, st);
+  }
+}
+
 extern "C" int dp_cache_update(dp_stage_t* s, int32_t first_frame, int32_t n_frames, void* hip_stream) {
   if (!s) return fail(DP_EINVAL, "dp_cache_update: null stage");
   if (n_frames == 0) { s->cache_len = 0; return DP_OK; }
@@ -492,11 +510,37 @@ extern "C" int dp_cache_update(dp_stage_t* s, int32_t first_frame, int32_t n_fra
   if (first_frame < 0 || (int64_t)first_frame + n_frames > s->last_frames)
     return fail(DP_EINVAL, "dp_cache_update: frames [%d, %lld) outside the last block's %d frames", first_frame,
                 (long long)first_frame + n_frames, s->last_frames);
-  // nothing is copied: the frames stay where the last forward wrote them and the next block goes around them
-  (void)hip_stream;
-  s->cache0 = s->blk0 + s->tok * first_frame;
-  s->cache_len = s->tok * n_frames;
+  const int64_t c0 = s->blk0 + s->tok * first_frame, nc = s->tok * n_frames;
+  if (c0 >= s->Smax || c0 + nc + s->Smax <= s->Lfit) {
+    // the usual case (always, in the paper's geometry): the frames stay where the last forward wrote them and
+    // the next block goes directly before or after them; nothing is copied
+    s->cache0 = c0; s->cache_len = nc;
+    return DP_OK;
+  }
+  // A maximal block would fit on neither side: copy the range into the free space beside the last block, at the
+  // buffer's start if the last block leaves nc positions free there, else at its end.  One of the two always
+  // holds (the buffer has Smax + 2 Ncmax positions, the last block at most Smax, the range lies inside it), and a
+  // maximal block then fits behind / before the copy.  The last block stays intact, so a further dp_cache_update
+  // can still name other frames of it.
+  const int64_t dst = s->blk0 >= nc ? 0 : s->Lfit - nc;
+  if (dst != 0 && s->blk0 + s->last_S > dst) return fail(DP_ESTATE, "dp_cache_update: no free space for the retained range");
+  hipStream_t st = (hipStream_t)hip_stream;
+  (void)hipGetLastError();
+  const bool prof = s->prof.begin(DP_PROF_CACHE_COPY, st);
+  if (s->cfg.dtype == DP_BF16) move_cache<bf16_t>(s, c0, dst, nc, st); else move_cache<float>(s, c0, dst, nc, st);
+  if (prof) s->prof.end(DP_PROF_CACHE_COPY, st);
+  const hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return fail(DP_EHIP, "dp_cache_update: %s", hipGetErrorString(err));
+  s->cache0 = dst; s->cache_len = nc;
   return DP_OK;
+}
+
+extern "C" size_t dp_stage_kv_bytes(const dp_stage_config* cfg) {
+  const char* why = validate(cfg);
+  if (why) { fail(DP_EINVAL, "dp_stage_kv_bytes: %s", why); return 0; }
+  const int64_t tok = (int64_t)cfg->tok_h * cfg->tok_w, E = cfg->dtype == DP_BF16 ? 2 : 4;
+  const int64_t lpad = rup(tok * cfg->max_block_frames + 2 * tok * cfg->max_cache_frames, 64) + 64;
+  return (size_t)(2 * lpad * cfg->dim * E);
 }
 
 // ------------------------------------------------------------------------------------------ test hook

@@ -236,6 +236,54 @@ def test_extended_block_queue_matches_oracle(variant):
             o.cache_update(ref_sched[i + 1]["cache_first"], ref_sched[i + 1]["cache_frames"])
 
 
+@pytest.mark.parametrize("name", ["tiny", "small_bf16"])
+def test_cache_hand_over_copies_only_when_no_side_has_room(name):
+    """The per-layer key/value buffer holds max_block_frames + 2 * max_cache_frames frame positions (the live K/V
+    of the paper's memory analysis, Table 1).  In the paper's geometry the retained frames stay in place and
+    nothing is copied; a retained range that leaves room for a maximal block on neither side is copied to the
+    buffer's start or end.  Both targets, a re-selection of other frames after a copy, and the copy-free cycle
+    are driven here; every output and cache is compared with the oracle, and the library's profiling hook tells
+    whether a hand-over copied."""
+    cfg, w, text, _ = synth.make_case(name, seed=23, strong_gate=True)
+    dt = cfg["dtype"]
+    g = gpu_stage(cfg, w, text, max_block_frames=4, max_cache_frames=2, max_abs_frames=64)
+    o = oracle_stage(cfg, w, text)
+    gen = torch.Generator().manual_seed(24)
+    li = cfg["n_layers"] - 1
+
+    def fwd(nf, f0, t, tag):
+        x = synth.make_block(cfg, nf, gen)
+        check(f"{name}/{tag}", to_np(g.forward(to_dev(x, cfg), nf, f0, t)), o.forward(x.numpy(), nf, f0, t), dt)
+
+    def hand_over(first, n, expect_copy, tag):
+        g.profile_begin(["cache_copy"])
+        g.cache_update(first, n)
+        copied = "cache_copy" in g.profile_end()
+        assert copied == expect_copy, (tag, copied)
+        o.cache_update(first, n)
+        check(f"{name}/{tag}/cache_k", to_np(g.peek("cache_k", li)), o.cache[li][0], dt)
+        check(f"{name}/{tag}/cache_v", to_np(g.peek("cache_v", li)), o.cache[li][1], dt)
+
+    # the paper's cycle (blocks of 4 handing over their first 2 frames): never a copy
+    for i, f0 in enumerate([20, 16, 12, 8, 4]):
+        fwd(4, f0, 900.0 - 100 * i, f"cycle{i}")
+        hand_over(0, 2, False, f"cycle{i}")
+    # copy to the buffer's start: the block sits 2 frames in, frames 1..2 of it are retained
+    g.cache_update(0, 0); o.cache_update(0, 0)
+    fwd(4, 30, 700.0, "a0"); hand_over(0, 2, False, "a0")
+    fwd(4, 26, 650.0, "a1"); hand_over(1, 2, True, "a1")
+    fwd(4, 23, 600.0, "a2")
+    hand_over(2, 2, False, "a2 first choice")           # two hand-overs of the same block: the last one counts,
+    hand_over(1, 2, True, "a2 second choice")           # and the block's rows survived whatever the first one did
+    fwd(3, 21, 550.0, "a3")
+    # copy to the buffer's end: the block sits 1 frame in, its frames 2..3 are retained
+    g.cache_update(0, 0); o.cache_update(0, 0)
+    fwd(3, 40, 500.0, "b0"); hand_over(0, 1, False, "b0")
+    fwd(4, 36, 450.0, "b1"); hand_over(2, 2, True, "b1")
+    fwd(4, 34, 400.0, "b2"); hand_over(0, 2, False, "b2")
+    fwd(2, 32, 350.0, "b3")
+
+
 def test_error_paths_leave_gpu_alone():
     from paper_2505_21070_amd import binding as B
     cfg, w, text, blocks = synth.make_case("tiny", seed=0)

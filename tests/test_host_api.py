@@ -152,3 +152,22 @@ def test_product_never_touches_the_oracle():
     assert "oracle" in body                                   # the baseline leg is where it is used ...
     assert "from oracle" not in head and "import oracle" not in head
     assert "from oracle" not in tail and "import oracle" not in tail      # ... and nowhere else
+
+
+@pytest.mark.parametrize("name", ["wan1p3b_stage", "wan1p3b_full", "wan14b_stage", "tiny"])
+def test_key_value_memory_is_the_papers_bound(B, name):
+    """Table 1 / appendix memory analysis: a device's K/V memory is (Num_B + Num_C) * KV per layer, KV = one
+    frame's keys and values.  The library's per-layer key/value buffer (cached range + current block) is exactly
+    that many frame positions plus at most 127 positions of alignment padding, and the workspace grows by at
+    least that much per layer."""
+    from paper_2505_21070_amd import synth
+    cfg = synth.stage_config(name)
+    conf = B.make_config(cfg)
+    num_b, num_c = cfg["block_frames"], 2 * cfg["cache_frames"]
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+    frame_kv = 2 * cfg["tok_h"] * cfg["tok_w"] * cfg["dim"] * esz          # keys + values of one frame, one layer
+    bound = (num_b + num_c) * frame_kv
+    got = B.kv_bytes_per_layer(conf)
+    assert bound <= got <= bound + 2 * 127 * cfg["dim"] * esz, (got, bound)
+    more = B.make_config(dict(cfg, n_layers=cfg["n_layers"] + 1))
+    assert B.workspace_bytes(more) - B.workspace_bytes(conf) >= got
