@@ -49,3 +49,25 @@ def oracle_built():
     from oracle import build
     build.build()
     return True
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """DP_PARITY_REPORT=<file>: every GPU-vs-oracle comparison of the session (max-abs, max-rel, relative L2 of the
+    whole tensor and of the worst row) as JSON lines, plus a summary per storage type on stderr."""
+    path = os.environ.get("DP_PARITY_REPORT")
+    if not path:
+        return
+    import json
+    try:
+        from harness import REPORT
+    except ImportError:
+        return
+    with open(path, "w") as f:
+        for r in REPORT:
+            f.write(json.dumps(r) + "\n")
+    for dt in ("f32", "bf16"):
+        rows = [r for r in REPORT if r["dtype"] == dt]
+        if rows:
+            sys.stderr.write(f"[parity report] {dt}: {len(rows)} comparisons, worst max_abs {max(r['max_abs'] for r in rows):.3e}, "
+                             f"worst whole-tensor rel L2 {max(r['rel_l2'] for r in rows):.3e}, "
+                             f"worst single-row rel L2 {max(r['worst_row'] for r in rows):.3e}\n")

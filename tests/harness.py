@@ -12,8 +12,10 @@ BF16_REL_L2 = 2e-2   # ||gpu - ref||_2 / ||ref||_2 over the whole tensor
 # bound alone lets a completely wrong row of a large tensor pass (one row of 6240 weighs 1.3 %); this one does
 # not: a wrong row has a relative error of order 1.  Measured worst rows are listed next to the derivation of
 # the tolerances in the design notes.
-BF16_ROW_REL_L2 = 5e-2
+BF16_ROW_REL_L2 = 2e-2
 MIN_ROW = 64         # rows shorter than this are folded together before the per-row bound is taken
+REPORT = []          # every comparison of the session: (name, dtype, max_abs, max_rel, rel_l2, worst_row); conftest.py
+                     # writes it out when DP_PARITY_REPORT names a file
 
 
 def gpu_stage(cfg, weights, text, **kw):
@@ -71,6 +73,8 @@ def check(name, got, ref, dtype, report=None):
     worst_row, worst_at = row_errors(got, ref)
     if report is not None:
         report[name] = dict(max_abs=max_abs, max_rel=max_rel, rel_l2=rel_l2, worst_row=worst_row, worst_row_at=worst_at)
+    REPORT.append(dict(name=name, dtype=dtype, shape=list(got.shape), max_abs=max_abs, max_rel=max_rel, rel_l2=rel_l2,
+                       worst_row=worst_row))
     if dtype == "f32":
         bad = err > FP32_TOL * np.maximum(1.0, np.abs(ref))
         assert not bad.any(), f"{name}: {int(bad.sum())} elements beyond 1e-4 (max_abs {max_abs:.3e}, max_rel {max_rel:.3e})"
