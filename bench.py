@@ -109,6 +109,21 @@ def cpu_baseline(cfg, weights, text, x_block, budget_s=24.0):
                       f"before it); scaled by algorithmic flops to {S} tokens x {cfg['n_layers']} layers = {t_stage:.0f} s per step"}
 
 
+def build_stage(B, cfg, weights, text, **kw):
+    """The stage as a deployment holds it: on the bf16 path the weight matrices are handed over [out, in], the
+    layout the GEMMs read, so the library multiplies by them in place and the device keeps its model chunk once
+    (geometries whose dim or ffn_dim is no multiple of 256 take the [in, out] hand-over and the library's copies).
+    Uploaded layer by layer so that the transposition never holds more than one layer twice."""
+    td = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+    oi = cfg["dtype"] == "bf16" and cfg["dim"] % 256 == 0 and cfg["ffn_dim"] % 256 == 0
+    fix = B.weights_out_in if oi else (lambda w: w)
+    wd = fix(B.weights_to_device({"stage": weights["stage"], "layers": []}, cfg["dtype"]))
+    for lw in weights["layers"]:
+        wd["layers"].append(fix(B.weights_to_device({"stage": {}, "layers": [lw]}, cfg["dtype"]))["layers"][0])
+    conf = B.make_config(cfg, weight_layout="out_in" if oi else "in_out", **kw)
+    return conf, B.Stage(conf, wd, text.to("cuda", td).contiguous())
+
+
 def cache_ablation(args):
     """Informational: the shape of the paper's feature-cache ablation (Table 4, with / without cache) on one
     stage.  Num_B = Num_C = 8 latent frames as in the paper's experiments: with the cache a pass feeds
@@ -121,8 +136,7 @@ def cache_ablation(args):
     cfg, weights, text, _ = synth.make_case("wan1p3b_stage", seed=0, n_blocks=0)
     tok = cfg["tok_h"] * cfg["tok_w"]
     td = torch.bfloat16
-    conf = B.make_config(cfg, max_block_frames=num_b + num_c, max_cache_frames=num_c // 2, max_abs_frames=64)
-    stage = B.Stage(conf, B.weights_to_device(weights, cfg["dtype"]), text.to("cuda", td).contiguous())
+    conf, stage = build_stage(B, cfg, weights, text, max_block_frames=num_b + num_c, max_cache_frames=num_c // 2, max_abs_frames=64)
     gen = torch.Generator().manual_seed(3)
     video = synth.round_to(torch.randn((24 * tok, cfg["dim"]), generator=gen, dtype=torch.float32), "bf16").to("cuda", td)
     half = num_c // 2
@@ -177,7 +191,7 @@ def latent_step(args):
     cfg, weights, text, blocks = synth.make_case("wan1p3b_stage", seed=0, n_blocks=1)
     nf, nc, tok = cfg["block_frames"], cfg["cache_frames"], cfg["tok_h"] * cfg["tok_w"]
     td = torch.bfloat16
-    stage = B.Stage(B.make_config(cfg, max_abs_frames=64), B.weights_to_device(weights, cfg["dtype"]), text.to("cuda", td).contiguous())
+    _conf, stage = build_stage(B, cfg, weights, text, max_abs_frames=64)
     ew = synth.make_end_weights(cfg, C, 0)
     dev = {k: v.to("cuda", td).contiguous() for k, v in ew.items()}
     dev.update({k: weights["stage"][k].to("cuda", td).contiguous() for k in ("wt1", "bt1", "wt2", "bt2")})
@@ -235,8 +249,7 @@ def long_sweep(args):
     tok, td = cfg["tok_h"] * cfg["tok_w"], torch.bfloat16
     torch.cuda.reset_peak_memory_stats()
     free0, _total = torch.cuda.mem_get_info()
-    stage = B.Stage(B.make_config(cfg, max_block_frames=first, max_cache_frames=nc, max_abs_frames=frames + 7),
-                    B.weights_to_device(weights, cfg["dtype"]), text.to("cuda", td).contiguous())
+    _conf, stage = build_stage(B, cfg, weights, text, max_block_frames=first, max_cache_frames=nc, max_abs_frames=frames + 7)
     dev = {k: v.to("cuda", td).contiguous() for k, v in synth.make_end_weights(cfg, C, 0).items()}
     dev.update({k: weights["stage"][k].to("cuda", td).contiguous() for k in ("wt1", "bt1", "wt2", "bt2")})
     ends = B.Ends(cfg, dev, C, first)
@@ -327,8 +340,7 @@ def main():
     nf, nc, tok = cfg["block_frames"], cfg["cache_frames"], cfg["tok_h"] * cfg["tok_w"]
     S, Nc = nf * tok, nc * tok
     td = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
-    conf = B.make_config(cfg, max_abs_frames=64)
-    stage = B.Stage(conf, B.weights_to_device(weights, cfg["dtype"]), text.to("cuda", td).contiguous())
+    conf, stage = build_stage(B, cfg, weights, text, max_abs_frames=64)
     x_nb, x_cur = (b.to("cuda", td).contiguous() for b in blocks[:2])
     out = torch.empty_like(x_cur)
     # prime the cache the way the queue does: the neighbour (later, noisier) block runs first and hands
@@ -423,7 +435,8 @@ def main():
         "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": args.workload + (" (informational: one step = one 8-block queue sweep)" if queue else ""), "layers": cfg["n_layers"], "dim": cfg["dim"], "heads": cfg["n_heads"],
                    "head_dim": cfg["head_dim"], "ffn_dim": cfg["ffn_dim"], "block_tokens": S, "cached_tokens": Nc,
-                   "text_tokens": cfg["text_len"], "step": "dp_stage_forward + dp_cache_update"},
+                   "text_tokens": cfg["text_len"], "step": "dp_stage_forward + dp_cache_update",
+                   "weight_layout": "out_in" if conf.weight_layout else "in_out", "workspace_bytes": B.workspace_bytes(conf)},
         "roofline": roof,
         "attn_ffn_tflops": mf_flops / (mf_ms * 1e-3) / 1e12 if mf_ms else None,
         "attn_ffn_frac_of_bf16_peak": mf_flops / (mf_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if mf_ms else None,

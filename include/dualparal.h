@@ -35,6 +35,9 @@ typedef struct dp_stage dp_stage_t; /* opaque, host memory, owned by the library
 enum { DP_OK = 0, DP_EINVAL = -1, DP_ENOMEM = -2 /* workspace / output too small */,
        DP_ESTATE = -3 /* call out of order */, DP_EHIP = -4 /* a HIP call failed */ };
 enum { DP_F32 = 0, DP_BF16 = 1 };
+/* How the caller hands the weight matrices over (dp_layer_weights, dp_stage_weights). */
+enum { DP_WEIGHTS_IN_OUT = 0 /* row-major [in, out]; the bf16 path keeps its own [out, in] copies in the workspace */,
+       DP_WEIGHTS_OUT_IN = 1 /* row-major [out, in], as the bf16 GEMMs read them: used in place, no second copy   */ };
 
 /* Geometry of a stage.  All sizes in elements. */
 typedef struct {
@@ -52,9 +55,15 @@ typedef struct {
   float rope_theta;           /* rotary base, e.g. 1e4                                            */
   float eps;                  /* LayerNorm / RMSNorm epsilon, e.g. 1e-6                           */
   int32_t debug_taps;         /* nonzero: keep intermediate results of the last layer for dp_stage_peek */
+  int32_t weight_layout;      /* DP_WEIGHTS_IN_OUT or DP_WEIGHTS_OUT_IN (DP_BF16 with dim, ffn_dim % 256 == 0) */
 } dp_stage_config;
 
-/* Device pointers to one layer's weights (element type = dtype). */
+/* Device pointers to one layer's weights (element type = dtype).  Shapes below are those of DP_WEIGHTS_IN_OUT.
+ * With DP_WEIGHTS_OUT_IN every matrix of this struct is its transpose, row-major [out, in], 16-byte aligned:
+ * wo, cwq, cwk, cwv, cwo [dim, dim], w1 [ffn_dim, dim], w2 [dim, ffn_dim], and wq, wk, wv are the three row
+ * groups of ONE [3 * dim, dim] matrix (wk == wq + dim * dim elements, wv == wq + 2 * dim * dim; anything else is
+ * DP_EINVAL).  The stage then multiplies by the caller's memory directly, which halves the weight bytes a device
+ * holds (the memory analysis of Sec. 3.1 / Table 1 counts the model chunk once).  Vectors are the same in both. */
 typedef struct {
   const void* mod;                               /* [6, dim] rows: shift1, scale1, gate1, shift2, scale2, gate2 */
   const void *wq, *bq, *wk, *bk, *wv, *bv;       /* self-attention projections [dim, dim] / [dim]  */
@@ -65,7 +74,9 @@ typedef struct {
   const void *w1, *b1, *w2, *b2;                 /* FFN [dim, ffn_dim], [ffn_dim], [ffn_dim, dim], [dim] */
 } dp_layer_weights;
 
-/* Device pointers to the stage-level weights plus a HOST array of per-layer structs. */
+/* Device pointers to the stage-level weights plus a HOST array of per-layer structs.  With DP_WEIGHTS_OUT_IN
+ * the text MLP's wx1 is [dim, text_dim] and wx2 [dim, dim] ([out, in]); wt1, wt2 and wm feed matrix-vector
+ * products and stay [in, out] in both layouts. */
 typedef struct {
   const void *wt1, *bt1;       /* [freq_dim, dim], [dim]   timestep MLP, first layer               */
   const void *wt2, *bt2;       /* [dim, dim], [dim]                                                */

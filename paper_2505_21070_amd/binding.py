@@ -18,6 +18,7 @@ _lib = C.CDLL(LIB_PATH)
 
 DP_OK, DP_EINVAL, DP_ENOMEM, DP_ESTATE, DP_EHIP = 0, -1, -2, -3, -4
 DP_F32, DP_BF16 = 0, 1
+WEIGHT_LAYOUT = {"in_out": 0, "out_in": 1}
 ORDER = {"reverse": 0, "sequential": 1}
 PEEK = dict(k=0, v=1, cache_k=2, cache_v=3, q=4, attn=5, cross_attn=6, x_self=7, x_cross=8, mod=9,
             text_k=10, text_v=11, x_res=12)
@@ -31,7 +32,7 @@ class StageConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "dim", "n_heads", "head_dim", "ffn_dim", "text_len",
                                          "text_dim", "tok_h", "tok_w", "max_block_frames", "max_cache_frames",
                                          "max_abs_frames", "dtype", "freq_dim")] + \
-               [("rope_theta", C.c_float), ("eps", C.c_float), ("debug_taps", C.c_int32)]
+               [("rope_theta", C.c_float), ("eps", C.c_float), ("debug_taps", C.c_int32), ("weight_layout", C.c_int32)]
 
 
 class LayerWeights(C.Structure):
@@ -141,7 +142,8 @@ def _check(code, where):
         raise DualParalError(code, where)
 
 
-def make_config(cfg, max_block_frames=None, max_cache_frames=None, max_abs_frames=4096, debug_taps=0):
+def make_config(cfg, max_block_frames=None, max_cache_frames=None, max_abs_frames=4096, debug_taps=0,
+                weight_layout="in_out"):
     """cfg: dict as produced by synth.stage_config."""
     c = StageConfig()
     for n in ("n_layers", "dim", "n_heads", "head_dim", "ffn_dim", "text_len", "text_dim", "tok_h", "tok_w", "freq_dim"):
@@ -153,6 +155,7 @@ def make_config(cfg, max_block_frames=None, max_cache_frames=None, max_abs_frame
     c.rope_theta = float(cfg["rope_theta"])
     c.eps = float(cfg["eps"])
     c.debug_taps = int(debug_taps)
+    c.weight_layout = WEIGHT_LAYOUT[weight_layout]
     return c
 
 
@@ -171,7 +174,8 @@ def _stream_handle(stream):
 
 class Stage:
     """One pipeline stage on the current device.  weights: {"stage": {...}, "layers": [{...}]} of device
-    tensors in the stage's dtype (contiguous, [in, out] matrices); text: device [text_len, text_dim]."""
+    tensors in the stage's dtype (contiguous; matrices [in, out], or as weights_out_in returns them when the
+    config says "out_in"); text: device [text_len, text_dim]."""
 
     def __init__(self, config, weights, text, stream=None):
         self.config = config
@@ -186,16 +190,18 @@ class Stage:
             return t.data_ptr()
 
         D, F, Td, fd = config.dim, config.ffn_dim, config.text_dim, config.freq_dim
+        oi = config.weight_layout == WEIGHT_LAYOUT["out_in"]
         sw = StageWeights()
         shapes = dict(wt1=(fd, D), bt1=(D,), wt2=(D, D), bt2=(D,), wm=(D, 6 * D), bm=(6 * D,),
-                      wx1=(Td, D), bx1=(D,), wx2=(D, D), bx2=(D,))
+                      wx1=(D, Td) if oi else (Td, D), bx1=(D,), wx2=(D, D), bx2=(D,))
         for n in STAGE_FIELDS:
             if n in weights["stage"]:
                 setattr(sw, n, ptr(weights["stage"][n], shapes[n]))
         arr = (LayerWeights * config.n_layers)()
         for i, lw in enumerate(weights["layers"]):
             for n in LAYER_FIELDS:
-                shape = (6, D) if n == "mod" else (D, F) if n == "w1" else (F,) if n == "b1" else (F, D) if n == "w2" \
+                shape = (6, D) if n == "mod" else ((F, D) if oi else (D, F)) if n == "w1" else (F,) if n == "b1" \
+                    else ((D, F) if oi else (F, D)) if n == "w2" \
                     else (D, D) if n in ("wq", "wk", "wv", "wo", "cwq", "cwk", "cwv", "cwo") else (D,)
                 setattr(arr[i], n, ptr(lw[n], shape))
         sw.layers = arr
@@ -415,6 +421,28 @@ def probe_stream_f32_bf16(n, iters=20, device="cuda"):
     _check(_lib.dp_probe_stream_f32_bf16(src.data_ptr(), dst.data_ptr(), n, iters, stream, C.byref(out)),
            "dp_probe_stream_f32_bf16")
     return out.value
+
+
+def weights_out_in(weights):
+    """Device weights with [in, out] matrices -> the same weights as the "out_in" layout wants them: every matrix
+    the GEMMs multiply by transposed to [out, in], q | k | v in one [3 * dim, dim] tensor (the three entries
+    are views of it).  The timestep MLP and the modulation head stay [in, out]."""
+    def t(m):
+        return m.t().contiguous()
+    st = dict(weights["stage"])
+    for n in ("wx1", "wx2"):
+        if n in st:
+            st[n] = t(st[n])
+    layers = []
+    for lw in weights["layers"]:
+        o = dict(lw)
+        D = lw["wq"].shape[0]
+        qkv = torch.cat([lw["wq"].t(), lw["wk"].t(), lw["wv"].t()], dim=0).contiguous()
+        o["wq"], o["wk"], o["wv"] = qkv[:D], qkv[D:2 * D], qkv[2 * D:]
+        for n in ("wo", "cwq", "cwk", "cwv", "cwo", "w1", "w2"):
+            o[n] = t(lw[n])
+        layers.append(o)
+    return {"stage": st, "layers": layers}
 
 
 def weights_to_device(weights, dtype, device="cuda"):

@@ -127,6 +127,12 @@ static const char* validate(const dp_stage_config* c) {
     const int64_t spad = rup((int64_t)c->tok_h * c->tok_w * c->max_block_frames, 256);
     if (rup(c->text_len, 256) > 3 * spad) return "text_len too large for the block size";
   }
+  if (c->weight_layout != DP_WEIGHTS_IN_OUT && c->weight_layout != DP_WEIGHTS_OUT_IN) return "unknown weight_layout";
+  if (c->weight_layout == DP_WEIGHTS_OUT_IN) {
+    // the GEMM tiles read whole groups of 256 weight rows: in the caller's memory there is no padding to read
+    if (c->dtype != DP_BF16) return "DP_WEIGHTS_OUT_IN is a layout of the bf16 path";
+    if (c->dim % 256 || c->ffn_dim % 256) return "DP_WEIGHTS_OUT_IN needs dim and ffn_dim % 256 == 0";
+  }
   if (c->dtype == DP_BF16) {
     if (c->dim % 64 || c->ffn_dim % 64 || c->text_dim % 64) return "bf16 path needs dim, ffn_dim, text_dim % 64 == 0";
     if (((int64_t)c->tok_h * c->tok_w) % 8) return "bf16 path needs tok_h * tok_w % 8 == 0";
@@ -161,7 +167,8 @@ static size_t carve(dp_stage* s, void* base) {
   s->ctx = cv.take(s->Ltpad * D * E);
   s->ctx_mid = cv.take(s->Ltpad * D * E);
   const int64_t kmax = c.text_dim > D ? c.text_dim : D;
-  s->wtmp = bf ? cv.take(rup(D, 256) * kmax * E) : nullptr;
+  const bool own = bf && c.weight_layout == DP_WEIGHTS_IN_OUT;   // the library keeps [out, in] copies of the matrices
+  s->wtmp = own ? cv.take(rup(D, 256) * kmax * E) : nullptr;
   s->heads_epi = bf && D % 256 == 0;
   s->ssq_np = (int)(D / 128);                         // most partial sums per row any tile shape produces
   s->qssq = s->heads_epi ? (float*)cv.take(s->Smax * s->ssq_np * 4) : nullptr;
@@ -199,7 +206,9 @@ static size_t carve(dp_stage* s, void* base) {
   if (bf) {
     for (int64_t l = 0; l < L; ++l) {
       LayerMem& m = s->lm[(size_t)l];
-      m.wqkv_t = cv.take(rup(3 * D, 256) * D * E); m.bqkv = cv.take(3 * D * E);
+      m.bqkv = cv.take(3 * D * E);
+      if (!own) continue;                               // handed over as [out, in]: read in place (see init_typed)
+      m.wqkv_t = cv.take(rup(3 * D, 256) * D * E);
       m.wo_t = cv.take(rup(D, 256) * D * E); m.cwq_t = cv.take(rup(D, 256) * D * E);
       m.cwo_t = cv.take(rup(D, 256) * D * E);
       m.w1_t = cv.take(rup(F, 256) * D * E); m.w2_t = cv.take(rup(D, 256) * F * E);
@@ -267,6 +276,7 @@ static void init_typed(dp_stage* s, const void* text, hipStream_t st) {
   const int64_t D = c.dim, F = c.ffn_dim, Lt = c.text_len, Td = c.text_dim;
   const int h = c.n_heads, d = c.head_dim;
   constexpr bool bf = sizeof(T) == 2;
+  const bool own = bf && c.weight_layout == DP_WEIGHTS_IN_OUT;
   launch_fill_zero(s->xres, zero_span(s), st);
   launch_rope_table(s->rope_f, c.max_abs_frames, s->rt.c_f, c.rope_theta, st);
   launch_rope_table(s->rope_y, c.tok_h, s->rt.c_h, c.rope_theta, st);
@@ -278,13 +288,20 @@ static void init_typed(dp_stage* s, const void* text, hipStream_t st) {
     launch_to_f32<T>((const T*)w.cgq, m.cgq, D, st); launch_to_f32<T>((const T*)w.cgk, m.cgk, D, st);
     launch_to_f32<T>((const T*)w.ln3_g, m.ln3g, D, st); launch_to_f32<T>((const T*)w.ln3_b, m.ln3b, D, st);
     if (bf) {
+      launch_copy2d<T>((const T*)w.bq, 0, (T*)m.bqkv, 0, 1, D, st);
+      launch_copy2d<T>((const T*)w.bk, 0, (T*)m.bqkv + D, 0, 1, D, st);
+      launch_copy2d<T>((const T*)w.bv, 0, (T*)m.bqkv + 2 * D, 0, 1, D, st);
+    }
+    if (bf && !own) {
+      // [out, in] already, q | k | v rows in one matrix (checked by dp_stage_init): the GEMMs read the caller's memory
+      m.wqkv_t = (void*)w.wq; m.wo_t = (void*)w.wo; m.cwq_t = (void*)w.cwq; m.cwo_t = (void*)w.cwo;
+      m.w1_t = (void*)w.w1; m.w2_t = (void*)w.w2;
+    }
+    if (own) {
       T* qkv = (T*)m.wqkv_t;
       launch_transpose_pad<T>((const T*)w.wq, D, D, qkv, D, st);
       launch_transpose_pad<T>((const T*)w.wk, D, D, qkv + D * D, D, st);
       launch_transpose_pad<T>((const T*)w.wv, D, D, qkv + 2 * D * D, rup(3 * D, 256) - 2 * D, st);
-      launch_copy2d<T>((const T*)w.bq, 0, (T*)m.bqkv, 0, 1, D, st);
-      launch_copy2d<T>((const T*)w.bk, 0, (T*)m.bqkv + D, 0, 1, D, st);
-      launch_copy2d<T>((const T*)w.bv, 0, (T*)m.bqkv + 2 * D, 0, 1, D, st);
       launch_transpose_pad<T>((const T*)w.wo, D, D, (T*)m.wo_t, rup(D, 256), st);
       launch_transpose_pad<T>((const T*)w.cwq, D, D, (T*)m.cwq_t, rup(D, 256), st);
       launch_transpose_pad<T>((const T*)w.cwo, D, D, (T*)m.cwo_t, rup(D, 256), st);
@@ -297,16 +314,16 @@ static void init_typed(dp_stage* s, const void* text, hipStream_t st) {
   launch_copy2d<T>((const T*)text, Td, (T*)s->textpad, Td, Lt, Td, st);
   const void* ctx = s->textpad;
   if (Td != D) {
-    if (bf) launch_transpose_pad<T>((const T*)s->w.wx1, Td, D, (T*)s->wtmp, rup(D, 256), st);
-    Path<T>::gemm(s->textpad, Td, s->w.wx1, s->wtmp, Lt, D, Td, EPI_GELU, epi_store(s->ctx_mid, D, s->w.bx1), st);
-    if (bf) launch_transpose_pad<T>((const T*)s->w.wx2, D, D, (T*)s->wtmp, rup(D, 256), st);
-    Path<T>::gemm(s->ctx_mid, D, s->w.wx2, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->ctx, D, s->w.bx2), st);
+    if (own) launch_transpose_pad<T>((const T*)s->w.wx1, Td, D, (T*)s->wtmp, rup(D, 256), st);
+    Path<T>::gemm(s->textpad, Td, s->w.wx1, own ? s->wtmp : s->w.wx1, Lt, D, Td, EPI_GELU, epi_store(s->ctx_mid, D, s->w.bx1), st);
+    if (own) launch_transpose_pad<T>((const T*)s->w.wx2, D, D, (T*)s->wtmp, rup(D, 256), st);
+    Path<T>::gemm(s->ctx_mid, D, s->w.wx2, own ? s->wtmp : s->w.wx2, Lt, D, D, EPI_STORE, epi_store(s->ctx, D, s->w.bx2), st);
     ctx = s->ctx;
   }
   for (int l = 0; l < c.n_layers; ++l) {
     const dp_layer_weights& w = s->lw[(size_t)l]; LayerMem& m = s->lm[(size_t)l];
-    if (bf) launch_transpose_pad<T>((const T*)w.cwk, D, D, (T*)s->wtmp, rup(D, 256), st);
-    Path<T>::gemm(ctx, D, w.cwk, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbk), st);
+    if (own) launch_transpose_pad<T>((const T*)w.cwk, D, D, (T*)s->wtmp, rup(D, 256), st);
+    Path<T>::gemm(ctx, D, w.cwk, own ? s->wtmp : w.cwk, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbk), st);
     { const NormRopeJob<T> jk{0, m.cgk, 1.f, (T*)m.tk, s->Ltpad * d, 0, 0};
       launch_norm_rope<T>((const T*)s->raw, D, Lt, h, d, c.eps, &jk, 1, nullptr, 0, 1, 1, st); }
     if (s->heads_epi) {
@@ -315,8 +332,8 @@ static void init_typed(dp_stage* s, const void* text, hipStream_t st) {
       const NormRopeJob<T> jk{0, m.cgqk, 1.f, (T*)m.tkq, s->Ltpad * d, 0, 0};
       launch_norm_rope<T>((const T*)s->raw, D, Lt, h, d, c.eps, &jk, 1, nullptr, 0, 1, 1, st);
     }
-    if (bf) launch_transpose_pad<T>((const T*)w.cwv, D, D, (T*)s->wtmp, rup(D, 256), st);
-    Path<T>::gemm(ctx, D, w.cwv, s->wtmp, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbv), st);
+    if (own) launch_transpose_pad<T>((const T*)w.cwv, D, D, (T*)s->wtmp, rup(D, 256), st);
+    Path<T>::gemm(ctx, D, w.cwv, own ? s->wtmp : w.cwv, Lt, D, D, EPI_STORE, epi_store(s->raw, D, w.cbv), st);
     launch_v_transpose<T>((const T*)s->raw, D, 0, Lt, h, d, (T*)m.tvt, s->Ltpad, 0, st);
   }
 }
@@ -337,6 +354,22 @@ extern "C" int dp_stage_init(const dp_stage_config* cfg, const dp_stage_weights*
     const void* const* p = (const void* const*)&weights->layers[l];
     for (size_t i = 0; i < sizeof(dp_layer_weights) / sizeof(void*); ++i)
       if (!p[i]) return fail(DP_EINVAL, "dp_stage_init: layer %d has a null weight pointer (field %zu)", l, i);
+  }
+  if (cfg->weight_layout == DP_WEIGHTS_OUT_IN) {
+    // read in place by 16-byte loads; q | k | v rows form the one matrix the fused projection multiplies by
+    const size_t dd = (size_t)cfg->dim * cfg->dim * 2;
+    auto misaligned = [](const void* p) { return ((uintptr_t)p & 15) != 0; };
+    if (cfg->text_dim != cfg->dim && (misaligned(weights->wx1) || misaligned(weights->wx2)))
+      return fail(DP_EINVAL, "dp_stage_init: DP_WEIGHTS_OUT_IN matrices must be 16-byte aligned");
+    for (int l = 0; l < cfg->n_layers; ++l) {
+      const dp_layer_weights& w = weights->layers[l];
+      if ((const char*)w.wk != (const char*)w.wq + dd || (const char*)w.wv != (const char*)w.wq + 2 * dd)
+        return fail(DP_EINVAL, "dp_stage_init: layer %d: DP_WEIGHTS_OUT_IN needs wq, wk, wv back to back in one "
+                               "[3 * dim, dim] matrix", l);
+      if (misaligned(w.wq) || misaligned(w.wo) || misaligned(w.cwq) || misaligned(w.cwk) || misaligned(w.cwv) ||
+          misaligned(w.cwo) || misaligned(w.w1) || misaligned(w.w2))
+        return fail(DP_EINVAL, "dp_stage_init: layer %d: DP_WEIGHTS_OUT_IN matrices must be 16-byte aligned", l);
+    }
   }
   dp_stage* s = new (std::nothrow) dp_stage();
   if (!s) return fail(DP_ENOMEM, "dp_stage_init: host allocation failed");

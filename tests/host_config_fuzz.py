@@ -14,7 +14,7 @@ class StageConfig(C.Structure):
     _fields_ = [(n, I32) for n in ("n_layers", "dim", "n_heads", "head_dim", "ffn_dim", "text_len", "text_dim",
                                    "tok_h", "tok_w", "max_block_frames", "max_cache_frames", "max_abs_frames",
                                    "dtype", "freq_dim")] + \
-               [("rope_theta", C.c_float), ("eps", C.c_float), ("debug_taps", I32)]
+               [("rope_theta", C.c_float), ("eps", C.c_float), ("debug_taps", I32), ("weight_layout", I32)]
 
 
 class EndsConfig(C.Structure):

@@ -171,3 +171,26 @@ def test_key_value_memory_is_the_papers_bound(B, name):
     assert bound <= got <= bound + 2 * 127 * cfg["dim"] * esz, (got, bound)
     more = B.make_config(dict(cfg, n_layers=cfg["n_layers"] + 1))
     assert B.workspace_bytes(more) - B.workspace_bytes(conf) >= got
+
+
+def test_out_in_weight_layout_validation_and_workspace(B):
+    """DP_WEIGHTS_OUT_IN: bf16 only, dim and ffn_dim multiples of 256 (no padding rows exist in the caller's
+    memory); the workspace then holds no weight matrix: with it, a device keeps its model chunk once (Sec. 2,
+    Table 1) and the per-layer growth of the workspace is K/V, text keys/values and vectors only."""
+    from paper_2505_21070_amd import synth
+    cfg = synth.stage_config("wan1p3b_stage")
+    io, oi = B.make_config(cfg), B.make_config(cfg, weight_layout="out_in")
+    D, F, L = cfg["dim"], cfg["ffn_dim"], cfg["n_layers"]
+    matrices = L * (6 * D * D + 2 * D * F) * 2
+    saved = B.workspace_bytes(io) - B.workspace_bytes(oi)
+    assert B.workspace_bytes(oi) > 0
+    assert matrices <= saved <= matrices + (1 << 20) + max(D, cfg["text_dim"]) * D * 2       # + the transposition buffer
+    per_layer = B.workspace_bytes(B.make_config(dict(cfg, n_layers=L + 1), weight_layout="out_in")) - B.workspace_bytes(oi)
+    assert per_layer < B.kv_bytes_per_layer(oi) + 4 * 512 * D * 2 + (1 << 20)                # K/V + text K/V (+ gains)
+    for bad in (dict(cfg, dtype="f32"), dict(cfg, ffn_dim=8960 + 64), synth.stage_config("small_bf16"),
+                synth.stage_config("tile192_bf16")):
+        assert B.workspace_bytes(B.make_config(bad, weight_layout="out_in")) == 0
+        assert B.last_error()
+    c = B.make_config(cfg)
+    c.weight_layout = 2
+    assert B.workspace_bytes(c) == 0 and "weight_layout" in B.last_error()
