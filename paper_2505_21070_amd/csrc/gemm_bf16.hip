@@ -566,6 +566,7 @@ static void launch_gemm_bf16_heads(const bf16_t* A, int64_t lda, const bf16_t* W
 bool launch_gemm_bf16(const bf16_t* A, int64_t lda, const bf16_t* Wt, int64_t ldw, int64_t M, int64_t N,
                       int64_t K, int epi, const EpiArgs& e, hipStream_t st) {
   if (M <= 0 || N <= 0) return true;
+  if (K < 64 || K % 64) return false;          // whole k-tiles of 64 (the callers validate their widths)
   if (epi == EPI_HEADS) {
     if (!e.heads || !gemm_bf16_heads_ok(M, N, *e.heads)) return false;
     launch_gemm_bf16_heads(A, lda, Wt, ldw, M, N, K, e, st);
