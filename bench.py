@@ -28,6 +28,8 @@ PEAK_HBM_GBS = 8000.0         # HBM3E, published
 # it was measured on: `src` names the source file and `sha` the first 16 hex digits of its SHA-256 at the time of
 # the profile.  With any other source (or no entry) the bench prints null instead of a stale figure.
 MEASURED_TRAFFIC = {
+    ("wan14b_stage", "self_attn"): {"bytes": 1.5602e+09, "src": "attn_bf16.hip", "sha": "870a6262f55fc09c"},
+    ("wan1p3b_stage", "self_attn"): {"bytes": 2.2954e+08, "src": "attn_bf16.hip", "sha": "870a6262f55fc09c"},
 }
 
 
