@@ -1,6 +1,7 @@
 // fp32 GEMM for the DP_F32 path: C = A[M,K] * W[K,N] with a fused epilogue.  Plain FMA arithmetic
 // (no matrix cores) so that results stay within fp32 rounding of the reference.
-// 64x64 tile per 256-thread block, 4x4 outputs per thread, K stepped by 16 through LDS.
+// 64x64 tile per 256-thread block, 4x4 outputs per thread, K stepped by 16 through LDS, the next step's
+// operands prefetched into registers.
 #include "kernels.h"
 
 template <int EPI>
@@ -13,23 +14,28 @@ __global__ __launch_bounds__(256) void k_gemm_f32(const float* __restrict__ A, i
   const int tx = tid & 15, ty = tid >> 4;        // thread owns rows ty*4.., cols tx*4..
   const int64_t m0 = (int64_t)blockIdx.x * 64, n0 = (int64_t)blockIdx.y * 64;   // rows on x: no 65535-block limit
   float acc[4][4] = {};
-  for (int64_t k0 = 0; k0 < K; k0 += 16) {
-    // A tile: 64 rows x 16 k ; thread loads 4 elements
+  // the next k-step's operands travel from global memory into registers while this one is multiplied
+  float ra[4], rw[4];
+  auto fetch = [&](int64_t k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i) {                // A tile: 64 rows x 16 k; W tile: 16 k x 64 columns
       const int idx = tid + i * 256;             // 0..1023
-      const int r = idx >> 4, kk = idx & 15;
-      const int64_t m = m0 + r, k = k0 + kk;
-      As[kk][r] = (m < M && k < K) ? A[m * lda + k] : 0.f;
+      const int64_t m = m0 + (idx >> 4), ka = k0 + (idx & 15);
+      ra[i] = (m < M && ka < K) ? A[m * lda + ka] : 0.f;
+      const int64_t kw = k0 + (idx >> 6), n = n0 + (idx & 63);
+      rw[i] = (kw < K && n < N) ? W[kw * ldw + n] : 0.f;
     }
+  };
+  fetch(0);
+  for (int64_t k0 = 0; k0 < K; k0 += 16) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int idx = tid + i * 256;
-      const int kk = idx >> 6, c = idx & 63;
-      const int64_t k = k0 + kk, n = n0 + c;
-      Ws[kk][c] = (k < K && n < N) ? W[k * ldw + n] : 0.f;
+      As[idx & 15][idx >> 4] = ra[i];
+      Ws[idx >> 6][idx & 63] = rw[i];
     }
     __syncthreads();
+    if (k0 + 16 < K) fetch(k0 + 16);
 #pragma unroll
     for (int kk = 0; kk < 16; ++kk) {
       float a[4], b[4];
