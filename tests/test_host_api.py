@@ -194,3 +194,35 @@ def test_out_in_weight_layout_validation_and_workspace(B):
     c = B.make_config(cfg)
     c.weight_layout = 2
     assert B.workspace_bytes(c) == 0 and "weight_layout" in B.last_error()
+
+
+def test_schedule_random_parameter_sweep_matches_oracle(B):
+    """Integer work, bit-exact: 300 seeded random queues (T, block count, Num_B, Num_C <= 2 Num_B, optional longer
+    first block; both orders, all three input variants) against the oracle's schedule (Sec. 3.1 - 3.3)."""
+    rng = np.random.default_rng(20250521)
+    for _ in range(300):
+        T, nb = int(rng.integers(1, 13)), int(rng.integers(1, 10))
+        num_b = int(rng.integers(1, 9))
+        num_c = 2 * int(rng.integers(0, num_b + 1))
+        first = int(rng.integers(num_b, num_b + 4)) if rng.random() < 0.3 else 0
+        order = ("reverse", "sequential")[int(rng.integers(2))]
+        variant = ("block", "extended", "nocache")[int(rng.integers(3))]
+        got = B.blockwise_schedule(T, nb, num_b, num_c, first, 1000.0, order, variant)
+        ref = oracle_schedule(T, nb, num_b, num_c, first or None, 1000.0, order, variant)
+        assert len(got) == len(ref) == T * nb
+        for g, r in zip(got, ref):
+            for k, v in r.items():
+                assert g[k] == (np.float32(v) if k == "timestep" else v), ((T, nb, num_b, num_c, first, order, variant), k, g, r)
+
+
+def test_noise_assignment_random_parameter_sweep_matches_oracle(B):
+    """300 seeded random (block count, Num_B, Num_C <= 2 Num_B) cases of the coordinated noise initialisation
+    (Sec. 3.3) against the oracle, index for index."""
+    from oracle.noise import noise_assignment
+    from paper_2505_21070_amd import synth
+    rng = np.random.default_rng(33)
+    for i in range(300):
+        nb, num_b = int(rng.integers(1, 12)), int(rng.integers(1, 10))
+        num_c = 2 * int(rng.integers(0, num_b + 1))
+        words = synth.shuffle_words((nb - 1) * max(num_b - 1, 0) + 2 * num_b + 2, 1000 + i)
+        assert B.noise_assign(nb, num_b, num_c, words) == noise_assignment(nb, num_b, num_c, words), (nb, num_b, num_c)
