@@ -18,7 +18,8 @@
  *  - Calls that take a stream are asynchronous on it and ordered by it.  One handle is used on
  *    one stream at a time.  `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
  *  - Element type of activations and weights is the config's dtype: DP_F32 (float) or DP_BF16
- *    (bfloat16, upper half of an IEEE float).  Matrices are row-major [in, out].
+ *    (bfloat16, upper half of an IEEE float).  Matrices are row-major [in, out]; a stage can also take
+ *    them [out, in] (dp_stage_config.weight_layout, see dp_layer_weights).
  */
 #ifndef DUALPARAL_H
 #define DUALPARAL_H
